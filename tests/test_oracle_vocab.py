@@ -1,0 +1,159 @@
+"""Pins for the oracle's vocabulary (Sec. 3.2, Eq. 2-4): worked examples, brute force, invariants."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def run_oracle(V, W, stream, T=(), split=None):
+    """active set after feeding `stream` (init on the first `split` ids, the rest by updates)."""
+    v = oracle.Vocab(V, W)
+    split = len(stream) if split is None else split
+    v.init(stream[:split], T)
+    for x in stream[split:]:
+        v.update([x])
+    return v.active().tolist()
+
+
+def brute(V, W, stream, T):
+    """independent O(V*W) membership test: v is active iff it sits at one of the last W stream
+    positions or is in T."""
+    out = []
+    L = len(stream)
+    for v in range(V):
+        hit = False
+        for back in range(1, W + 1):
+            p = L - back
+            if p < 0:
+                break
+            if stream[p] == v:
+                hit = True
+        for t in T:
+            if t == v:
+                hit = True
+        if hit:
+            out.append(v)
+    return out
+
+
+def parse_examples():
+    rows = []
+    for line in open(os.path.join(GOLD, "vocab_worked_examples.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        W, S, T, exp = [f.strip() for f in line.split("|")]
+        ints = lambda s: [] if s == "-" else [int(x) for x in s.split()]
+        rows.append((int(W), ints(S), ints(T), ints(exp)))
+    return rows
+
+
+@pytest.mark.parametrize("W,S,T,exp", parse_examples())
+def test_worked_examples(W, S, T, exp):
+    assert run_oracle(16, W, S, T) == exp
+    # the same stream fed token by token after an empty init gives the same set
+    assert run_oracle(16, W, S, T, split=0) == exp
+    assert brute(16, W, S, T) == exp
+
+
+def test_exhaustive_tiny():
+    """all streams of length <= 6 over 3 ids, all windows 1..4, against brute force."""
+    for L in range(0, 7):
+        for S in itertools.product(range(3), repeat=L):
+            for W in (1, 2, 3, 4):
+                assert run_oracle(3, W, list(S)) == brute(3, W, S, ())
+
+
+def test_fuzz_against_brute_force():
+    rng = np.random.default_rng(7)
+    for trial in range(300):
+        V = int(rng.integers(2, 64))
+        W = int(rng.integers(1, 9))
+        v = oracle.Vocab(V, W)
+        S = rng.integers(0, V, size=int(rng.integers(0, 20))).tolist()
+        T = rng.integers(0, V, size=int(rng.integers(0, 6))).tolist()
+        v.init(S, T)
+        assert v.active().tolist() == brute(V, W, S, T)
+        for step in range(12):
+            new = rng.integers(0, V, size=int(rng.integers(0, 2 * W + 2))).tolist()
+            if rng.random() < 0.4:
+                T = rng.integers(0, V, size=int(rng.integers(0, 6))).tolist()
+                v.update(new, T)
+            else:
+                v.update(new)
+            S = S + new
+            assert v.stream_len() == len(S)
+            assert v.active().tolist() == brute(V, W, S, T), (trial, step)
+
+
+def test_invariants():
+    rng = np.random.default_rng(11)
+    for trial in range(100):
+        V, W = 200, int(rng.integers(1, 40))
+        S = rng.integers(0, V, size=int(rng.integers(1, 120))).tolist()
+        T = rng.integers(0, V, size=int(rng.integers(0, 10))).tolist()
+        A = run_oracle(V, W, S, T)
+        assert A == sorted(set(A))                                   # ascending, unique
+        assert set(S[-W:]) <= set(A)                                 # every suffix token is active
+        assert set(T) <= set(A)
+        assert len(A) <= min(W, len(S)) + len(set(T))                # |I| <= W_max (+|T|)
+        assert set(A) == set(S[-W:]) | set(T)
+        if W >= len(S):
+            assert set(A) == set(S) | set(T)                         # short stream: taken whole
+        assert run_oracle(V, 1, S, T) == sorted({S[-1]} | set(T))    # W=1: last token only
+        # incremental updates == init on the full stream, whatever the split point
+        for split in (0, len(S) // 2, len(S)):
+            assert run_oracle(V, W, S, T, split=split) == A
+        # relabelling ids by a permutation maps the set through the permutation
+        pi = rng.permutation(V)
+        assert run_oracle(V, W, [int(pi[s]) for s in S], [int(pi[t]) for t in T]) == sorted(int(pi[a]) for a in A)
+        # order and multiplicity of T's elements are irrelevant
+        assert run_oracle(V, W, S, list(reversed(T)) + T) == A
+
+
+def test_recency_eviction():
+    """a token leaves exactly when its most recent occurrence leaves the window (text after Eq. 4)."""
+    V, W = 50, 5
+    v = oracle.Vocab(V, W)
+    v.init([7])
+    for i in range(1, W):                  # 7 is still among the last W ids
+        v.update([10 + i])
+        assert 7 in v.active()
+    v.update([30])                         # now W newer ids follow it
+    assert 7 not in v.active()
+    v.update([7])                          # re-appended: back in
+    assert 7 in v.active()
+
+
+def test_update_replaces_T_wholesale_and_keeps_it_otherwise():
+    v = oracle.Vocab(100, 2)
+    v.init([1, 2], [50, 60])
+    v.update([3])
+    assert v.active().tolist() == [2, 3, 50, 60]
+    v.update([], [70])
+    assert v.active().tolist() == [2, 3, 70]
+    v.update([4], [])
+    assert v.active().tolist() == [3, 4]
+
+
+def test_out_of_range_ids_hold_a_position_but_are_not_members():
+    v = oracle.Vocab(10, 2)
+    v.init([1, 2, 99])
+    assert v.active().tolist() == [2]
+    v.update([-5], [3, 10, -1])
+    assert v.active().tolist() == [3]
+
+
+def test_window_bound_paper_setting():
+    """W_max = 3072 (Sec. 4.1): the active set never exceeds it however long the stream grows."""
+    rng = np.random.default_rng(3)
+    v = oracle.Vocab(128256, 3072)
+    v.init(rng.integers(0, 128256, size=5000))
+    for _ in range(5):
+        v.update(rng.integers(0, 128256, size=2000))
+        assert len(v.active()) <= 3072

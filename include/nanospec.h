@@ -1,0 +1,168 @@
+/*
+ * nanospec.h -- C ABI of the NanoSpec draft-step hot path for AMD MI355X (gfx950).
+ *
+ * The library keeps a context-aware active vocabulary on the GPU, projects draft hidden states
+ * onto the active rows of the bf16 LM-head matrix, and selects the top-k draft tokens.  It
+ * follows the problem statement of the NanoSpec paper (arXiv 2605.26444):
+ *
+ *   Eq. 1   z = W_head h                       dense head (the comparison point)
+ *   Sec 3.1 z' = W_head[I_t, :] h              sparse head on the active rows only
+ *   Eq. 2-3 candidate stream S, appended to at prefill and after every verification
+ *   Eq. 4   I_t = Unique(Suffix(S, W_max))     active index set, recency eviction
+ *   Alg. 1  SelectDraftTokens(z', I)           top-k over z' mapped back to global ids
+ *
+ * Conventions
+ *   - Token ids are 0-based int32 in [0, V).
+ *   - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  The caller owns every
+ *     buffer it passes in; the library owns the state object and frees it in nanospec_destroy.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Every call
+ *     documented as "asynchronous" only enqueues kernels on that stream: it never synchronises
+ *     the host, never allocates and never frees, so it may be recorded into a HIP graph.
+ *   - All functions return a nanospec_status; nothing aborts or throws.  Argument errors are
+ *     found on the host before anything is launched, in which case nothing is enqueued.
+ *   - A state object must not be used from two streams at once.
+ *   - bf16 = upper 16 bits of an IEEE fp32.  Products are accumulated in fp32.
+ */
+#ifndef NANOSPEC_H_
+#define NANOSPEC_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define NANOSPEC_API __attribute__((visibility("default")))
+#else
+#define NANOSPEC_API
+#endif
+
+typedef struct nanospec_state nanospec_state; /* opaque; owns all device-resident state */
+typedef int32_t nanospec_status;
+
+enum {
+  NANOSPEC_OK = 0,
+  NANOSPEC_EINVAL = -1,    /* null pointer, non-positive size, unsupported shape, bad offsets   */
+  NANOSPEC_ENOMEM = -2,    /* device or host allocation failed (nanospec_create only)           */
+  NANOSPEC_ECAPACITY = -3, /* an input exceeds a capacity fixed at nanospec_create              */
+  NANOSPEC_EHIP = -4       /* a HIP runtime call failed                                         */
+};
+
+/* Bits reported by nanospec_last_device_error. */
+enum {
+  NANOSPEC_DEV_BAD_ID = 1 /* an appended or candidate id was outside [0, V); it was ignored     */
+};
+
+/* Largest batch (independent sequences per state) supported: per-sequence offsets travel as
+ * kernel arguments so that no call needs a host-to-device copy. */
+#define NANOSPEC_MAX_BATCH 256
+
+/* Human-readable name of a status code (static storage). */
+NANOSPEC_API const char* nanospec_status_string(nanospec_status s);
+
+/* Byte sizes of the device buffers a state with these parameters owns.  Pure host arithmetic
+ * (usable without a GPU); nanospec_create allocates exactly these.  For the paper's Llama-3.1-8B
+ * setting (V=128256, W_max=3072) the bitmap is ceil(V/32)*4 = 16032 B and the stream ring
+ * 3072*4 = 12288 B, the "16 KB" and "12 KB" rows of Table 6; `gathered_bytes_at_cap` is the size
+ * the paper's repack buffer would have (window * d * 2; 24 MiB there), which this library never
+ * allocates because the gather is fused into the projection. */
+typedef struct nanospec_layout {
+  int64_t ring_bytes;            /* per sequence: last `window` stream ids, int32                */
+  int64_t counter_bytes;         /* per sequence: window multiplicity of every id, uint32[V]     */
+  int64_t window_bitmap_bytes;   /* per sequence: 1 bit per id, set iff multiplicity > 0         */
+  int64_t topk_bitmap_bytes;     /* per sequence: 1 bit per id, set iff id is in the set T       */
+  int64_t ids_bytes;             /* per sequence: ascending active ids, int32[capacity]          */
+  int64_t scalars_bytes;         /* per sequence: n, ring position, fill                         */
+  int64_t workspace_bytes;       /* whole state: split-K partial logits + top-k candidates       */
+  int64_t total_bytes;           /* everything, all sequences                                    */
+  int64_t gathered_bytes_at_cap; /* window * d * 2: what a packed copy of the rows would take    */
+  int32_t capacity;              /* row stride of ids / logits: max |I_t| rounded up to 64       */
+} nanospec_layout;
+
+NANOSPEC_API nanospec_status nanospec_state_layout(int32_t V, int32_t d, int32_t batch, int32_t window,
+                                      int32_t topk_cap, int32_t m_cap, int32_t k_cap,
+                                      nanospec_layout* out);
+
+/* Create the device-resident state for `batch` independent sequences on the current device.
+ *   V         vocabulary size (rows of W_head)            d        hidden size, multiple of 8
+ *   window    W_max of Eq. 4                               topk_cap largest |T| per sequence
+ *   m_cap     largest number of draft hidden rows per sequence and call
+ *   k_cap     largest k of nanospec_topk_remap (<= 64)
+ * Synchronous (allocates).  The state starts empty: stream length 0, T empty, I empty. */
+NANOSPEC_API nanospec_status nanospec_create(nanospec_state** out, int32_t V, int32_t d, int32_t batch,
+                                int32_t window, int32_t topk_cap, int32_t m_cap, int32_t k_cap);
+NANOSPEC_API nanospec_status nanospec_destroy(nanospec_state* st);
+
+/* Stream initialisation, Eq. 2 and the first I of Alg. 1: for sequence b the stream becomes
+ * ctx_ids[h_ctx_off[b] .. h_ctx_off[b+1]) (only its last `window` ids matter) and the candidate
+ * set T becomes topk_ids[h_topk_off[b] .. h_topk_off[b+1]) (duplicates allowed, order
+ * irrelevant).  The active set I = Unique(Suffix(S, window)) U T is left on the device as an
+ * ascending id list with its count.  The paper appends top-K candidates to the stream itself;
+ * that mode is T = empty with those ids appended through ctx/new ids.
+ *   d_ctx_ids, d_topk_ids : device int32; may be NULL when every range is empty.
+ *   h_ctx_off, h_topk_off : host int32[batch+1], non-decreasing, read before the call returns.
+ * Errors: EINVAL (null state/offsets, decreasing offsets), ECAPACITY (a T range > topk_cap).
+ * Asynchronous.  Ids outside [0,V) hold their stream position but never become members; they
+ * raise NANOSPEC_DEV_BAD_ID. */
+NANOSPEC_API nanospec_status nanospec_vocab_init(nanospec_state* st, const int32_t* d_ctx_ids, const int32_t* h_ctx_off,
+                                    const int32_t* d_topk_ids, const int32_t* h_topk_off, void* hip_stream);
+
+/* Stream update, Eq. 3 followed by Eq. 4: append new_ids[h_new_off[b] .. h_new_off[b+1]) to the
+ * stream of sequence b (zero ids is legal), evict what leaves the window, and rebuild the
+ * ascending active list and its count -- one launch for the whole batch.  If d_topk_ids is not
+ * NULL (or h_topk_off is not NULL with all-empty ranges) the set T of every sequence is replaced
+ * wholesale; pass both NULL to keep T.  Same argument rules and errors as nanospec_vocab_init.
+ * Asynchronous. */
+NANOSPEC_API nanospec_status nanospec_vocab_update(nanospec_state* st, const int32_t* d_new_ids, const int32_t* h_new_off,
+                                      const int32_t* d_topk_ids, const int32_t* h_topk_off, void* hip_stream);
+
+/* Borrowed device views of the active vocabulary, valid until nanospec_destroy; contents are
+ * valid in stream order after the last init/update.
+ *   *d_ids : int32[batch][capacity], row b holds I of sequence b ascending in [0, n_b)
+ *   *d_n   : int32[batch]            |I| per sequence
+ *   *capacity : row stride (also the row stride of the logits of nanospec_sparse_head). */
+NANOSPEC_API nanospec_status nanospec_vocab_view(const nanospec_state* st, const int32_t** d_ids, const int32_t** d_n,
+                                    int32_t* capacity);
+
+/* Sparse head, Eq. 1 restricted to the active rows (Sec. 3.1):
+ *   logits[b][m][j] = sum_c W[ids_b[j]][c] * H[b][m][c]   for j < n_b, fp32 accumulation.
+ *   d_W_bf16  : bf16 [V][d] row-major by token id          d_H_bf16 : bf16 [batch][M][d]
+ *   d_logits  : fp32 [batch][M][capacity]; entries j >= n_b are unspecified.
+ * The rows are gathered inside the projection; no packed copy of them is made.  The result for a
+ * given (W row, H row) pair does not depend on j, on n or on the other active ids.
+ * Errors: EINVAL (null, M < 1), ECAPACITY (M > m_cap).  Asynchronous. */
+NANOSPEC_API nanospec_status nanospec_sparse_head(nanospec_state* st, const void* d_W_bf16, const void* d_H_bf16, int32_t M,
+                                     float* d_logits, void* hip_stream);
+
+/* Draft-token selection, SelectDraftTokens(z', I) of Alg. 1 with the operator T_K of Sec. 3.2:
+ * for every (b, m) the k largest of logits[b][m][0..n_b), ordered by value descending then global
+ * id ascending (+0 and -0 tie), written as global ids and values.  Slots beyond n_b get id -1
+ * and value -inf.  NaN logits are not supported.
+ *   d_out_ids : int32 [batch][M][k]       d_out_vals : fp32 [batch][M][k] (may be NULL)
+ * Errors: EINVAL, ECAPACITY (M > m_cap or k > k_cap).  Asynchronous. */
+NANOSPEC_API nanospec_status nanospec_topk_remap(nanospec_state* st, const float* d_logits, int32_t M, int32_t k,
+                                    int32_t* d_out_ids, float* d_out_vals, void* hip_stream);
+
+/* Dense full-vocabulary head, Eq. 1: logits[m][v] = sum_c W[v][c] * H[m][c] for all v < V.
+ *   d_logits : fp32 [M_total][V].  Stateless.  Errors: EINVAL (null, sizes < 1, d % 8 != 0).
+ * Asynchronous. */
+NANOSPEC_API nanospec_status nanospec_dense_head(const void* d_W_bf16, const void* d_H_bf16, int32_t V, int32_t d,
+                                    int32_t M_total, float* d_logits, void* hip_stream);
+
+/* Top-k over dense logits (the selection step of the full-vocabulary comparison point):
+ * rows [M_total][V], ids are the column indices; same ordering rule as nanospec_topk_remap.
+ *   d_workspace : device scratch of at least nanospec_dense_topk_workspace(V, M_total, k) bytes.
+ * Errors: EINVAL (null, sizes < 1, k > 64), ECAPACITY (workspace too small).  Asynchronous. */
+NANOSPEC_API int64_t nanospec_dense_topk_workspace(int32_t V, int32_t M_total, int32_t k);
+NANOSPEC_API nanospec_status nanospec_dense_topk(const float* d_logits, int32_t V, int32_t M_total, int32_t k,
+                                    int32_t* d_out_ids, float* d_out_vals, void* d_workspace,
+                                    int64_t workspace_bytes, void* hip_stream);
+
+/* Read and clear the sticky device error flags (NANOSPEC_DEV_* bits).  Synchronises `hip_stream`. */
+NANOSPEC_API nanospec_status nanospec_last_device_error(nanospec_state* st, int32_t* flags, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NANOSPEC_H_ */

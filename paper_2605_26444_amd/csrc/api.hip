@@ -1,0 +1,233 @@
+// C ABI of libnanospec: argument checking, state allocation, kernel dispatch.
+#include <new>
+
+#include "common.h"
+
+using namespace nanospec;
+
+namespace {
+
+inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// split-K partial logits are only used while the row count is small; bound their footprint.
+constexpr int kSplitRowsMax = 16384;
+constexpr int kSplitMax = 16;
+
+bool fill_layout(int32_t V, int32_t d, int32_t batch, int32_t window, int32_t topk_cap, int32_t m_cap, int32_t k_cap,
+                 nanospec_layout* L) {
+  if (V < 1 || d < 8 || d % 8 != 0 || batch < 1 || batch > NANOSPEC_MAX_BATCH || window < 1 || topk_cap < 0 ||
+      m_cap < 1 || k_cap < 1 || k_cap > kMaxK)
+    return false;
+  const int64_t nwords = round_up((V + 31) / 32, 4);
+  int64_t maxn = (int64_t)window + topk_cap;
+  if (maxn > V) maxn = V;
+  const int64_t cap = round_up(maxn, 64);
+  if (cap > (int64_t)kTopkChunk * 16) return false;
+  L->capacity = (int32_t)cap;
+  L->ring_bytes = (int64_t)window * 4;
+  L->counter_bytes = (int64_t)V * 4;
+  L->window_bitmap_bytes = nwords * 4;
+  L->topk_bitmap_bytes = nwords * 4;
+  L->ids_bytes = cap * 4;
+  L->scalars_bytes = 3 * 4;
+  const int64_t srows = cap < kSplitRowsMax ? cap : kSplitRowsMax;
+  const int64_t partial = (int64_t)kSplitMax * batch * m_cap * srows * 4;
+  const int64_t tws = topk_workspace_bytes((int32_t)cap, batch * m_cap, k_cap);
+  L->workspace_bytes = round_up(partial, 256) + round_up(tws, 256);
+  const int64_t per_seq = round_up(L->ring_bytes, 256) + round_up(L->counter_bytes, 256) +
+                          2 * round_up(L->window_bitmap_bytes, 256) + round_up(L->ids_bytes, 256);
+  L->total_bytes = per_seq * batch + round_up(3 * 4 * (int64_t)batch, 256) + 256 + L->workspace_bytes;
+  L->gathered_bytes_at_cap = (int64_t)window * d * 2;
+  return true;
+}
+
+nanospec_status offsets_to_arg(const int32_t* h_off, int batch, Offsets* out, int64_t per_seq_limit, bool* any) {
+  *any = false;
+  for (int i = 0; i <= NANOSPEC_MAX_BATCH; ++i) out->v[i] = 0;
+  if (!h_off) return NANOSPEC_OK;
+  for (int b = 0; b <= batch; ++b) out->v[b] = h_off[b];
+  if (h_off[0] < 0) return NANOSPEC_EINVAL;
+  for (int b = 0; b < batch; ++b) {
+    const int64_t len = (int64_t)h_off[b + 1] - h_off[b];
+    if (len < 0) return NANOSPEC_EINVAL;
+    if (per_seq_limit >= 0 && len > per_seq_limit) return NANOSPEC_ECAPACITY;
+    if (len > 0) *any = true;
+  }
+  return NANOSPEC_OK;
+}
+
+nanospec_status vocab_call(nanospec_state* st, const int32_t* d_new, const int32_t* h_noff, const int32_t* d_topk,
+                           const int32_t* h_toff, bool is_init, void* stream) {
+  if (!st) return NANOSPEC_EINVAL;
+  if (is_init && !h_noff) return NANOSPEC_EINVAL;
+  Offsets noff, toff;
+  bool any_new = false, any_t = false;
+  nanospec_status rc = offsets_to_arg(h_noff, st->batch, &noff, -1, &any_new);
+  if (rc != NANOSPEC_OK) return rc;
+  rc = offsets_to_arg(h_toff, st->batch, &toff, st->topk_cap, &any_t);
+  if (rc != NANOSPEC_OK) return rc;
+  if (any_new && !d_new) return NANOSPEC_EINVAL;
+  if (any_t && !d_topk) return NANOSPEC_EINVAL;
+  if (d_topk && !h_toff) return NANOSPEC_EINVAL;
+  const int replace_T = (is_init || h_toff != nullptr) ? 1 : 0;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (is_init) {
+    if (launch_vocab_clear(st, s) != hipSuccess) return NANOSPEC_EHIP;
+  }
+  if (launch_vocab_apply(st, d_new, noff, d_topk, toff, replace_T, s) != hipSuccess) return NANOSPEC_EHIP;
+  return NANOSPEC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* nanospec_status_string(nanospec_status s) {
+  switch (s) {
+    case NANOSPEC_OK: return "ok";
+    case NANOSPEC_EINVAL: return "invalid argument";
+    case NANOSPEC_ENOMEM: return "out of memory";
+    case NANOSPEC_ECAPACITY: return "capacity exceeded";
+    case NANOSPEC_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+nanospec_status nanospec_state_layout(int32_t V, int32_t d, int32_t batch, int32_t window, int32_t topk_cap,
+                                      int32_t m_cap, int32_t k_cap, nanospec_layout* out) {
+  if (!out) return NANOSPEC_EINVAL;
+  return fill_layout(V, d, batch, window, topk_cap, m_cap, k_cap, out) ? NANOSPEC_OK : NANOSPEC_EINVAL;
+}
+
+nanospec_status nanospec_create(nanospec_state** out, int32_t V, int32_t d, int32_t batch, int32_t window,
+                                int32_t topk_cap, int32_t m_cap, int32_t k_cap) {
+  if (!out) return NANOSPEC_EINVAL;
+  *out = nullptr;
+  nanospec_layout L;
+  if (!fill_layout(V, d, batch, window, topk_cap, m_cap, k_cap, &L)) return NANOSPEC_EINVAL;
+  nanospec_state* st = new (std::nothrow) nanospec_state();
+  if (!st) return NANOSPEC_ENOMEM;
+  st->V = V; st->d = d; st->batch = batch; st->window = window;
+  st->topk_cap = topk_cap; st->m_cap = m_cap; st->k_cap = k_cap;
+  st->layout = L;
+  if (hipGetDevice(&st->device) != hipSuccess) { delete st; return NANOSPEC_EHIP; }
+  if (hipMalloc(reinterpret_cast<void**>(&st->base), L.total_bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    delete st;
+    return NANOSPEC_ENOMEM;
+  }
+  if (hipHostMalloc(reinterpret_cast<void**>(&st->h_err_pinned), 64, hipHostMallocDefault) != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipFree(st->base);
+    delete st;
+    return NANOSPEC_ENOMEM;
+  }
+  char* p = st->base;
+  auto take = [&](int64_t bytes) { char* r = p; p += round_up(bytes, 256); return r; };
+  VocabPtrs& vp = st->vp;
+  vp.V = V; vp.window = window; vp.nwords = (int32_t)(L.window_bitmap_bytes / 4); vp.cap = L.capacity;
+  vp.ring = reinterpret_cast<int32_t*>(take(round_up(L.ring_bytes, 256) * batch));
+  vp.cnt = reinterpret_cast<uint32_t*>(take(round_up(L.counter_bytes, 256) * batch));
+  vp.wbit = reinterpret_cast<uint32_t*>(take(round_up(L.window_bitmap_bytes, 256) * batch));
+  vp.tbit = reinterpret_cast<uint32_t*>(take(round_up(L.topk_bitmap_bytes, 256) * batch));
+  vp.ids = reinterpret_cast<int32_t*>(take(round_up(L.ids_bytes, 256) * batch));
+  int32_t* sc = reinterpret_cast<int32_t*>(take(3 * 4 * (int64_t)batch));
+  vp.n = sc; vp.pos = sc + batch; vp.fill = sc + 2 * batch;
+  vp.err = reinterpret_cast<int32_t*>(take(4));
+  const int64_t srows = L.capacity < kSplitRowsMax ? L.capacity : kSplitRowsMax;
+  st->partial_bytes = (int64_t)kSplitMax * batch * m_cap * srows * 4;
+  st->partial = reinterpret_cast<float*>(take(st->partial_bytes));
+  st->topk_ws_bytes = topk_workspace_bytes(L.capacity, batch * m_cap, k_cap);
+  st->topk_ws = take(st->topk_ws_bytes);
+  if (p - st->base > L.total_bytes || vocab_configure(st) != hipSuccess || hipMemset(vp.err, 0, 4) != hipSuccess ||
+      launch_vocab_clear(st, nullptr) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipHostFree(st->h_err_pinned);
+    (void)hipFree(st->base);
+    delete st;
+    return NANOSPEC_EHIP;
+  }
+  *out = st;
+  return NANOSPEC_OK;
+}
+
+nanospec_status nanospec_destroy(nanospec_state* st) {
+  if (!st) return NANOSPEC_EINVAL;
+  hipError_t e1 = hipFree(st->base);
+  hipError_t e2 = hipHostFree(st->h_err_pinned);
+  delete st;
+  return (e1 == hipSuccess && e2 == hipSuccess) ? NANOSPEC_OK : NANOSPEC_EHIP;
+}
+
+nanospec_status nanospec_vocab_init(nanospec_state* st, const int32_t* d_ctx_ids, const int32_t* h_ctx_off,
+                                    const int32_t* d_topk_ids, const int32_t* h_topk_off, void* hip_stream) {
+  return vocab_call(st, d_ctx_ids, h_ctx_off, d_topk_ids, h_topk_off, true, hip_stream);
+}
+
+nanospec_status nanospec_vocab_update(nanospec_state* st, const int32_t* d_new_ids, const int32_t* h_new_off,
+                                      const int32_t* d_topk_ids, const int32_t* h_topk_off, void* hip_stream) {
+  return vocab_call(st, d_new_ids, h_new_off, d_topk_ids, h_topk_off, false, hip_stream);
+}
+
+nanospec_status nanospec_vocab_view(const nanospec_state* st, const int32_t** d_ids, const int32_t** d_n,
+                                    int32_t* capacity) {
+  if (!st) return NANOSPEC_EINVAL;
+  if (d_ids) *d_ids = st->vp.ids;
+  if (d_n) *d_n = st->vp.n;
+  if (capacity) *capacity = st->vp.cap;
+  return NANOSPEC_OK;
+}
+
+nanospec_status nanospec_sparse_head(nanospec_state* st, const void* d_W_bf16, const void* d_H_bf16, int32_t M,
+                                     float* d_logits, void* hip_stream) {
+  if (!st || !d_W_bf16 || !d_H_bf16 || !d_logits || M < 1) return NANOSPEC_EINVAL;
+  if (M > st->m_cap) return NANOSPEC_ECAPACITY;
+  hipError_t e = launch_head(d_W_bf16, d_H_bf16, st->vp.ids, st->vp.n, 0, st->vp.cap, st->batch, M, st->d, st->vp.cap,
+                             st->vp.cap, d_logits, st->partial, st->partial_bytes, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;
+}
+
+nanospec_status nanospec_topk_remap(nanospec_state* st, const float* d_logits, int32_t M, int32_t k, int32_t* d_out_ids,
+                                    float* d_out_vals, void* hip_stream) {
+  if (!st || !d_logits || !d_out_ids || M < 1 || k < 1) return NANOSPEC_EINVAL;
+  if (M > st->m_cap || k > st->k_cap) return NANOSPEC_ECAPACITY;
+  hipError_t e = launch_topk(d_logits, st->vp.cap, st->vp.ids, st->vp.cap, st->vp.n, 0, st->vp.cap, st->batch, M, k,
+                             d_out_ids, d_out_vals, st->topk_ws, st->topk_ws_bytes, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;
+}
+
+nanospec_status nanospec_dense_head(const void* d_W_bf16, const void* d_H_bf16, int32_t V, int32_t d, int32_t M_total,
+                                    float* d_logits, void* hip_stream) {
+  if (!d_W_bf16 || !d_H_bf16 || !d_logits || V < 1 || d < 8 || d % 8 != 0 || M_total < 1) return NANOSPEC_EINVAL;
+  hipError_t e = launch_head(d_W_bf16, d_H_bf16, nullptr, nullptr, V, V, 1, M_total, d, V, 0, d_logits, nullptr, 0,
+                             static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;
+}
+
+int64_t nanospec_dense_topk_workspace(int32_t V, int32_t M_total, int32_t k) {
+  if (V < 1 || M_total < 1 || k < 1 || k > kMaxK) return -1;
+  const int64_t b = topk_workspace_bytes(V, M_total, k);
+  return b > 256 ? b : 256;
+}
+
+nanospec_status nanospec_dense_topk(const float* d_logits, int32_t V, int32_t M_total, int32_t k, int32_t* d_out_ids,
+                                    float* d_out_vals, void* d_workspace, int64_t workspace_bytes, void* hip_stream) {
+  if (!d_logits || !d_out_ids || !d_workspace || V < 1 || M_total < 1 || k < 1 || k > kMaxK) return NANOSPEC_EINVAL;
+  if ((int64_t)V > (int64_t)kTopkChunk * 16) return NANOSPEC_EINVAL;
+  if (workspace_bytes < nanospec_dense_topk_workspace(V, M_total, k)) return NANOSPEC_ECAPACITY;
+  hipError_t e = launch_topk(d_logits, V, nullptr, 0, nullptr, V, V, 1, M_total, k, d_out_ids, d_out_vals,
+                             static_cast<char*>(d_workspace), workspace_bytes, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;
+}
+
+nanospec_status nanospec_last_device_error(nanospec_state* st, int32_t* flags, void* hip_stream) {
+  if (!st || !flags) return NANOSPEC_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (hipMemcpyAsync(st->h_err_pinned, st->vp.err, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return NANOSPEC_EHIP;
+  if (hipMemsetAsync(st->vp.err, 0, 4, s) != hipSuccess) return NANOSPEC_EHIP;
+  if (hipStreamSynchronize(s) != hipSuccess) return NANOSPEC_EHIP;
+  *flags = *st->h_err_pinned;
+  return NANOSPEC_OK;
+}
+
+}  // extern "C"

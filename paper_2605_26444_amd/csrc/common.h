@@ -1,0 +1,68 @@
+// Internal declarations shared by the translation units of libnanospec (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "nanospec.h"
+
+namespace nanospec {
+
+constexpr int kVocabThreads = 1024;   // one workgroup per sequence in the vocabulary kernel
+constexpr int kTopkThreads = 1024;    // single-pass top-k workgroup
+constexpr int kTopkChunk = 16384;     // elements per workgroup in the two-pass top-k
+constexpr int kMaxK = 64;
+
+// Per-sequence offsets travel by value in the kernel argument block (no H2D copy, graph-safe).
+struct Offsets {
+  int32_t v[NANOSPEC_MAX_BATCH + 1];
+};
+
+struct VocabPtrs {
+  int32_t* ring;        // [batch][window]
+  uint32_t* cnt;        // [batch][V]
+  uint32_t* wbit;       // [batch][nwords]
+  uint32_t* tbit;       // [batch][nwords]
+  int32_t* ids;         // [batch][cap]
+  int32_t* n;           // [batch]
+  int32_t* pos;         // [batch] next ring slot
+  int32_t* fill;        // [batch] valid ring entries
+  int32_t* err;         // [1] sticky flags
+  int32_t V, window, nwords, cap;
+};
+
+}  // namespace nanospec
+
+struct nanospec_state {
+  int32_t V, d, batch, window, topk_cap, m_cap, k_cap;
+  int32_t device;
+  nanospec_layout layout;
+  nanospec::VocabPtrs vp;
+  char* base;               // the one device allocation everything lives in
+  float* partial;           // split-K partial logits
+  char* topk_ws;            // two-pass top-k candidates
+  int64_t partial_bytes, topk_ws_bytes;
+  int32_t* h_err_pinned;    // pinned host word for reading the device flags
+  int vocab_lds_bytes;
+};
+
+namespace nanospec {
+
+// vocab.hip
+hipError_t launch_vocab_clear(const nanospec_state* st, hipStream_t s);
+hipError_t launch_vocab_apply(const nanospec_state* st, const int32_t* d_new, const Offsets& noff,
+                              const int32_t* d_topk, const Offsets& toff, int replace_T, hipStream_t s);
+hipError_t vocab_configure(nanospec_state* st);
+
+// head.hip
+// logits[b][m][j] for j < n_b (n read on the device).  ids == nullptr: identity list of n_fixed rows.
+hipError_t launch_head(const void* W, const void* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
+                       int32_t cap_rows, int32_t batch, int32_t M, int32_t d, int64_t ld_logits,
+                       int64_t ids_stride, float* logits, float* partial, int64_t partial_bytes, hipStream_t s);
+
+// topk.hip
+int64_t topk_workspace_bytes(int32_t cap, int32_t rows, int32_t k);
+hipError_t launch_topk(const float* logits, int64_t ld, const int32_t* ids, int64_t ids_stride, const int32_t* n_dev,
+                       int32_t n_fixed, int32_t cap, int32_t batch, int32_t M, int32_t k, int32_t* out_ids,
+                       float* out_vals, char* ws, int64_t ws_bytes, hipStream_t s);
+
+}  // namespace nanospec

@@ -1,0 +1,186 @@
+// Context-aware active vocabulary kept on the GPU (paper Sec. 3.2 Eq. 2-4, Sec. 3.3 "GPU-resident
+// state management").
+//
+// Per sequence the state is: a ring of the last `window` stream ids, a multiplicity counter per
+// token id (how many times it occurs inside the window), a window bitmap (counter > 0), a bitmap of
+// the extra candidate set T, and the compacted ascending id list I with its count.  One workgroup
+// per sequence applies an update in ONE launch: counters are adjusted with atomics for every id that
+// leaves or enters the window, bits are fixed only after all counter updates have landed (so an id
+// that is evicted and re-appended in the same call ends up correct), and the union bitmap is
+// compacted with popcounts and a workgroup prefix scan.  Both bitmaps live in LDS during the kernel.
+#include "common.h"
+
+namespace nanospec {
+
+__global__ __launch_bounds__(256) void vocab_clear_kernel(VocabPtrs p, int batch) {
+  const size_t tid = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  const size_t ncnt = (size_t)batch * p.V;
+  for (size_t i = tid; i < ncnt; i += stride) p.cnt[i] = 0u;
+  const size_t nbit = (size_t)batch * p.nwords;
+  for (size_t i = tid; i < nbit; i += stride) {
+    p.wbit[i] = 0u;
+    p.tbit[i] = 0u;
+  }
+  for (size_t i = tid; i < (size_t)batch; i += stride) {
+    p.n[i] = 0;
+    p.pos[i] = 0;
+    p.fill[i] = 0;
+  }
+}
+
+__device__ __forceinline__ int wave_incl_scan(int x, int lane) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    int y = __shfl_up(x, o);
+    if (lane >= o) x += y;
+  }
+  return x;
+}
+
+__global__ __launch_bounds__(kVocabThreads) void vocab_apply_kernel(VocabPtrs p, const int32_t* __restrict__ new_ids,
+                                                                    Offsets noff, const int32_t* __restrict__ topk,
+                                                                    Offsets toff, int replace_T) {
+  extern __shared__ uint32_t lds[];
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nwords = p.nwords, V = p.V, W = p.window;
+  uint32_t* wb = lds;
+  uint32_t* tb = lds + nwords;
+  int* sc = reinterpret_cast<int*>(tb + nwords);   // 16 wave totals
+
+  uint32_t* gw = p.wbit + (size_t)b * nwords;
+  uint32_t* gt = p.tbit + (size_t)b * nwords;
+  uint32_t* cnt = p.cnt + (size_t)b * V;
+  int32_t* ring = p.ring + (size_t)b * W;
+
+  // bitmaps -> LDS
+  for (int i = tid * 4; i < nwords; i += kVocabThreads * 4) {
+    *reinterpret_cast<uint4*>(wb + i) = *reinterpret_cast<const uint4*>(gw + i);
+    *reinterpret_cast<uint4*>(tb + i) = replace_T ? make_uint4(0, 0, 0, 0) : *reinterpret_cast<const uint4*>(gt + i);
+  }
+
+  const int a = noff.v[b + 1] - noff.v[b];
+  const int32_t* src = new_ids + noff.v[b];
+  const int pos = p.pos[b], fill = p.fill[b];
+  const int skip = a > W ? a - W : 0;      // ids that enter and leave the window within this call
+  const int ae = a - skip;
+  int n_evict = fill + ae - W;
+  if (n_evict < 0) n_evict = 0;
+  int oldest = pos - fill;
+  if (oldest < 0) oldest += W;
+  int bad = 0;
+
+  // counters: -1 for every id leaving the window, +1 for every id entering it
+  for (int i = tid; i < n_evict; i += kVocabThreads) {
+    int slot = oldest + i;
+    if (slot >= W) slot -= W;
+    const int e = ring[slot];
+    if (e >= 0) atomicSub(&cnt[e], 1u);
+  }
+  for (int i = tid; i < skip; i += kVocabThreads) bad |= ((unsigned)src[i] >= (unsigned)V);
+  for (int i = tid; i < ae; i += kVocabThreads) {
+    const int v = src[skip + i];
+    if ((unsigned)v < (unsigned)V) atomicAdd(&cnt[v], 1u);
+    else bad = 1;
+  }
+  __threadfence();
+  __syncthreads();
+
+  // bits: window bit = (counter > 0), decided only now that every +1/-1 has landed
+  for (int i = tid; i < n_evict; i += kVocabThreads) {
+    int slot = oldest + i;
+    if (slot >= W) slot -= W;
+    const int e = ring[slot];
+    if (e >= 0) {
+      const uint32_t c = __hip_atomic_load(&cnt[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (c == 0u) atomicAnd(&wb[e >> 5], ~(1u << (e & 31)));
+    }
+  }
+  for (int i = tid; i < ae; i += kVocabThreads) {
+    const int v = src[skip + i];
+    if ((unsigned)v < (unsigned)V) atomicOr(&wb[v >> 5], 1u << (v & 31));
+  }
+  if (replace_T) {
+    const int nt = toff.v[b + 1] - toff.v[b];
+    const int32_t* ts = topk + toff.v[b];
+    for (int i = tid; i < nt; i += kVocabThreads) {
+      const int t = ts[i];
+      if ((unsigned)t < (unsigned)V) atomicOr(&tb[t >> 5], 1u << (t & 31));
+      else bad = 1;
+    }
+  }
+  __syncthreads();
+
+  // ring: the new ids overwrite the slots of the evicted ones (read above, before this barrier)
+  for (int i = tid; i < ae; i += kVocabThreads) {
+    int slot = pos + i;
+    if (slot >= W) slot -= W;
+    const int v = src[skip + i];
+    ring[slot] = ((unsigned)v < (unsigned)V) ? v : -1;
+  }
+
+  // compaction of (window | T): popcount per thread, workgroup exclusive scan, ascending emission
+  const int wpt = (((nwords + kVocabThreads - 1) / kVocabThreads) + 3) & ~3;
+  const int w0 = tid * wpt;
+  int mine = 0;
+  for (int i = w0; i < w0 + wpt && i < nwords; ++i) mine += __popc(wb[i] | tb[i]);
+  const int incl = wave_incl_scan(mine, lane);
+  if (lane == 63) sc[wave] = incl;
+  __syncthreads();
+  int off = incl - mine, total = 0;
+  for (int w = 0; w < kVocabThreads / 64; ++w) {
+    const int t = sc[w];
+    if (w < wave) off += t;
+    total += t;
+  }
+  int32_t* ids = p.ids + (size_t)b * p.cap;
+  for (int i = w0; i < w0 + wpt && i < nwords; ++i) {
+    uint32_t x = wb[i] | tb[i];
+    while (x) {
+      const int bit = __ffs(x) - 1;
+      if (off < p.cap) ids[off] = i * 32 + bit;
+      ++off;
+      x &= x - 1;
+    }
+  }
+  // bitmaps back to HBM
+  for (int i = tid * 4; i < nwords; i += kVocabThreads * 4) {
+    *reinterpret_cast<uint4*>(gw + i) = *reinterpret_cast<const uint4*>(wb + i);
+    if (replace_T) *reinterpret_cast<uint4*>(gt + i) = *reinterpret_cast<const uint4*>(tb + i);
+  }
+  if (tid == 0) {
+    p.n[b] = total < p.cap ? total : p.cap;
+    int np = pos + ae;
+    if (np >= W) np -= W;
+    p.pos[b] = np;
+    const int nf = fill + ae;
+    p.fill[b] = nf < W ? nf : W;
+  }
+  if (bad) atomicOr(p.err, (int)NANOSPEC_DEV_BAD_ID);
+}
+
+hipError_t vocab_configure(nanospec_state* st) {
+  st->vocab_lds_bytes = (2 * st->vp.nwords + 32) * 4;
+  if (st->vocab_lds_bytes > 160 * 1024 - 512) return hipErrorInvalidValue;
+  if (st->vocab_lds_bytes > 48 * 1024)
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(vocab_apply_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, st->vocab_lds_bytes);
+  return hipSuccess;
+}
+
+hipError_t launch_vocab_clear(const nanospec_state* st, hipStream_t s) {
+  size_t work = (size_t)st->batch * st->V;
+  int blocks = (int)((work + 255) / 256);
+  if (blocks > 4096) blocks = 4096;
+  vocab_clear_kernel<<<blocks, 256, 0, s>>>(st->vp, st->batch);
+  return hipGetLastError();
+}
+
+hipError_t launch_vocab_apply(const nanospec_state* st, const int32_t* d_new, const Offsets& noff,
+                              const int32_t* d_topk, const Offsets& toff, int replace_T, hipStream_t s) {
+  vocab_apply_kernel<<<st->batch, kVocabThreads, st->vocab_lds_bytes, s>>>(st->vp, d_new, noff, d_topk, toff,
+                                                                           replace_T);
+  return hipGetLastError();
+}
+
+}  // namespace nanospec

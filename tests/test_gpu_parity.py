@@ -1,0 +1,274 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import oracle
+from paper_2605_26444_amd import binding as B
+from paper_2605_26444_amd import synth
+
+from harness import (ATOL, RTOL, assert_logits_close, check_topk, csr, dev, dev_bf16, dev_ids, host_W,
+                     run_workload)
+
+pytestmark = pytest.mark.gpu
+
+
+def test_c1_tiny_every_step():
+    st = run_workload(synth.CONFIGS["c1"])
+    assert st["steps_checked"] == 9 and st.get("rows_checked_e2e", 0) > 0
+
+
+def test_c2_llama8b_head_every_step():
+    cfg = synth.CONFIGS["c2"]
+    st = run_workload(cfg)
+    n = np.array(st["n"])
+    assert abs(n[0, 0] - 3000) <= 60                      # |active| ~ 3k as the workload states
+    assert st["steps_checked"] == cfg["steps"] + 1
+    print("c2", st["max_err"], st.get("rows_near_tie", 0))
+
+
+def test_c3_qwen7b_head_wide_tree():
+    cfg = synth.CONFIGS["c3"]
+    st = run_workload(cfg, check_steps=set(range(0, 64, 4)) | {63})
+    print("c3", st["max_err"], st.get("rows_near_tie", 0))
+
+
+def test_c4_batch64_vocab_stress():
+    cfg = synth.CONFIGS["c4"]
+    st = run_workload(cfg, check_steps={0, 1, 127} | set(range(16, 128, 16)))
+    assert len(st["n"]) == cfg["steps"] + 1                # ids compared on every step
+    print("c4", st["max_err"], np.mean(st["n"]))
+
+
+@pytest.mark.parametrize("target", synth.CONFIGS["c5"]["targets"])
+def test_c5_sparsity_sweep(target):
+    cfg = synth.CONFIGS["c5"]
+    st = run_workload(cfg, target=target)
+    assert st["n"][0][0] == target
+    print("c5", target, st["max_err"])
+
+
+def test_dense_head_and_topk_small_full_check():
+    cfg = synth.CONFIGS["c1"]
+    W = host_W(cfg)
+    V, d, M, k = cfg["V"], cfg["d"], 5, 8
+    H = synth.make_H(cfg, 99, 1, M)[0]
+    dW, dH = dev_bf16(W), dev_bf16(H)
+    logits = torch.empty((M, V), dtype=torch.float32, device="cuda")
+    B.nanospec_dense_head(dW, dH, V, d, M, logits)
+    ws_bytes = B.nanospec_dense_topk_workspace(V, M, k)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    oi_d = torch.empty((M, k), dtype=torch.int32, device="cuda")
+    ov_d = torch.empty((M, k), dtype=torch.float32, device="cuda")
+    B.nanospec_dense_topk(logits, V, M, k, oi_d, ov_d, ws, ws_bytes)
+    torch.cuda.synchronize()
+    g = logits.cpu().numpy()
+    o32, o64 = oracle.head(W, H, omp=True)
+    assert_logits_close(g, o64, o32, "dense c1")
+    stats = {}
+    allids = np.arange(V, dtype=np.int32)
+    for m in range(M):
+        check_topk(oi_d.cpu().numpy()[m], ov_d.cpu().numpy()[m], g[m], o32[m], allids, k, stats, f"dense row {m}")
+
+
+def test_dense_head_full_size_sampled():
+    """V=128256, d=4096 dense head in the shape the benchmark times; oracle on sampled rows."""
+    cfg = synth.CONFIGS["c2"]
+    W = host_W(cfg)
+    V, d, M, k = cfg["V"], cfg["d"], cfg["M"], cfg["k"]
+    H = synth.make_H(cfg, 7, 1, M)[0]
+    dW, dH = dev_bf16(W), dev_bf16(H)
+    logits = torch.empty((M, V), dtype=torch.float32, device="cuda")
+    B.nanospec_dense_head(dW, dH, V, d, M, logits)
+    ws_bytes = B.nanospec_dense_topk_workspace(V, M, k)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    oi_d = torch.empty((M, k), dtype=torch.int32, device="cuda")
+    ov_d = torch.empty((M, k), dtype=torch.float32, device="cuda")
+    B.nanospec_dense_topk(logits, V, M, k, oi_d, ov_d, ws, ws_bytes)
+    torch.cuda.synchronize()
+    g = logits.cpu().numpy()
+    rng = np.random.default_rng(0)
+    sample = np.unique(np.concatenate([rng.choice(V, 4000, replace=False), [0, 1, V - 2, V - 1],
+                                       oi_d.cpu().numpy().ravel()])).astype(np.int32)
+    o32, o64 = oracle.head(W, H, ids=sample, omp=True)
+    assert_logits_close(g[:, sample], o64, o32, "dense c2 sampled")
+    allids = np.arange(V, dtype=np.int32)
+    for m in range(M):                                       # selection checked exactly on the GPU's logits
+        ei, ev = oracle.topk(g[m], allids, k)
+        assert np.array_equal(oi_d.cpu().numpy()[m], ei) and np.array_equal(ov_d.cpu().numpy()[m], ev)
+
+
+def _small_state(V=1000, d=64, batch=1, window=8, topk_cap=4, m_cap=3, k_cap=64):
+    return B.State(V, d, batch, window, topk_cap, m_cap, k_cap)
+
+
+def test_edge_cases_vocab():
+    st = _small_state()
+    o = oracle.Vocab(1000, 8)
+    # empty init: n == 0
+    B.nanospec_vocab_init(st.h, None, [0, 0], None, [0, 0])
+    o.init([], [])
+    assert len(st.read_active()[0]) == 0
+    # zero-length update is legal; update with only a T replacement
+    B.nanospec_vocab_update(st.h, None, [0, 0])
+    B.nanospec_vocab_update(st.h, None, [0, 0], dev(np.array([5, 5, 7], np.int32)), [0, 3])
+    o.update([], [5, 5, 7])
+    assert np.array_equal(st.read_active()[0], o.active())
+    # more new ids than the window holds; duplicates; id evicted and re-appended in one call
+    new = np.array([1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 3, 3, 900], np.int32)
+    B.nanospec_vocab_update(st.h, dev(new), [0, len(new)])
+    o.update(new)
+    assert np.array_equal(st.read_active()[0], o.active())
+    new = np.array([7, 8, 9, 10, 11, 3, 3, 900], np.int32)       # evicts exactly what it re-appends
+    B.nanospec_vocab_update(st.h, dev(new), [0, len(new)])
+    o.update(new)
+    assert np.array_equal(st.read_active()[0], o.active())
+    new = np.array([42] * 8, np.int32)                              # all-duplicate append fills the window
+    B.nanospec_vocab_update(st.h, dev(new), [0, 8], None, [0, 0])
+    o.update(new, [])
+    assert np.array_equal(st.read_active()[0], o.active()) and st.read_active()[0].tolist() == [42]
+    assert B.nanospec_last_device_error(st.h) == 0
+    # out-of-range ids: flagged, hold a stream position, never members
+    new = np.array([1, 1000, -3, 2], np.int32)
+    B.nanospec_vocab_update(st.h, dev(new), [0, 4], dev(np.array([2000, 6], np.int32)), [0, 2])
+    o.update(new, [2000, 6])
+    assert np.array_equal(st.read_active()[0], o.active())
+    assert B.nanospec_last_device_error(st.h) == B.DEV_BAD_ID
+    assert B.nanospec_last_device_error(st.h) == 0                  # reading clears the flags
+    # re-init discards everything
+    B.nanospec_vocab_init(st.h, dev(np.array([9, 9, 8], np.int32)), [0, 3], None, [0, 0])
+    o.init([9, 9, 8], [])
+    assert np.array_equal(st.read_active()[0], o.active())
+    st.close()
+
+
+def test_vocab_fuzz_ragged_batch():
+    rng = np.random.default_rng(5)
+    V, W, Bn = 5000, 37, 7
+    st = B.State(V, 64, Bn, W, 20, 2, 4)
+    orc = [oracle.Vocab(V, W) for _ in range(Bn)]
+    ctx = [rng.integers(0, 300, size=int(rng.integers(0, 120))).astype(np.int32) for _ in range(Bn)]
+    T = [rng.integers(0, V, size=int(rng.integers(0, 21))).astype(np.int32) for _ in range(Bn)]
+    f, off = csr(ctx)
+    tf, toff = csr(T)
+    B.nanospec_vocab_init(st.h, dev_ids(f), off, dev_ids(tf), toff)
+    for b in range(Bn):
+        orc[b].init(ctx[b], T[b])
+    for step in range(60):
+        new = [rng.integers(0, 300, size=int(rng.integers(0, 90 if step % 10 == 0 else 9))).astype(np.int32) for _ in range(Bn)]
+        f, off = csr(new)
+        if step % 3 == 0:
+            T = [rng.integers(0, V, size=int(rng.integers(0, 21))).astype(np.int32) for _ in range(Bn)]
+            tf, toff = csr(T)
+            B.nanospec_vocab_update(st.h, dev_ids(f), off, dev_ids(tf), toff)
+        else:
+            B.nanospec_vocab_update(st.h, dev_ids(f), off)
+        act = st.read_active()
+        for b in range(Bn):
+            orc[b].update(new[b], T[b] if step % 3 == 0 else None)
+            assert np.array_equal(act[b], orc[b].active()), (step, b)
+    st.close()
+
+
+def test_head_and_topk_edge_cases():
+    V, d, M = 1000, 64, 3
+    W = synth.normal_bf16(77, 0, (V, d), 0.02, threads=1)
+    W[10] = W[20]                                             # duplicate rows -> exact ties
+    W[30] = W[20]
+    H = synth.normal_bf16(77, 1, (M, d), 1.0, threads=1)
+    dW, dH = dev_bf16(W), dev_bf16(H)
+    st = B.State(V, d, 1, 16, 8, M, 64)
+    cap = st.capacity
+    logits = torch.full((1, M, cap), float("nan"), dtype=torch.float32, device="cuda")
+    for k in (1, 5, 64):
+        oi = torch.empty((1, M, k), dtype=torch.int32, device="cuda")
+        ov = torch.empty((1, M, k), dtype=torch.float32, device="cuda")
+        # n == 0: nothing active, all slots padded
+        B.nanospec_vocab_init(st.h, None, [0, 0], None, [0, 0])
+        B.nanospec_sparse_head(st.h, dW, dH, M, logits)
+        B.nanospec_topk_remap(st.h, logits, M, k, oi, ov)
+        torch.cuda.synchronize()
+        assert (oi.cpu().numpy() == -1).all() and np.isneginf(ov.cpu().numpy()).all()
+        # a handful of ids including the tied rows; k > n pads
+        ctx = np.array([30, 20, 10, 500, 999, 0], np.int32)
+        B.nanospec_vocab_init(st.h, dev(ctx), [0, len(ctx)], dev(np.array([7], np.int32)), [0, 1])
+        B.nanospec_sparse_head(st.h, dW, dH, M, logits)
+        B.nanospec_topk_remap(st.h, logits, M, k, oi, ov)
+        torch.cuda.synchronize()
+        act = st.read_active()[0]
+        assert act.tolist() == [0, 7, 10, 20, 30, 500, 999]
+        g = logits.cpu().numpy()[0]
+        o32, o64 = oracle.head(W, H, ids=act)
+        assert_logits_close(g[:, :7], o64, o32)
+        assert np.array_equal(g[:, 2], g[:, 3]) and np.array_equal(g[:, 3], g[:, 4])   # duplicate rows: identical bits
+        for m in range(M):
+            ei, ev = oracle.topk(g[m, :7], act, k)
+            assert np.array_equal(oi.cpu().numpy()[0, m], ei) and np.array_equal(ov.cpu().numpy()[0, m], ev)
+    st.close()
+
+
+def test_topk_all_equal_and_signed_zero():
+    V, d, M, k = 4096, 8, 2, 6
+    st = B.State(V, d, 1, 4096, 0, M, 64)
+    ctx = np.arange(0, 4096, 3, dtype=np.int32)
+    B.nanospec_vocab_init(st.h, dev(ctx), [0, len(ctx)], None, [0, 0])
+    n, cap = len(ctx), st.capacity
+    vals = np.zeros((1, M, cap), np.float32)
+    vals[0, 0, :n] = 1.25                                     # all equal: the k lowest ids win
+    vals[0, 1, :n] = np.where(np.arange(n) % 2 == 0, -0.0, 0.0)   # +0 and -0 tie
+    lg = dev(vals)
+    oi = torch.empty((1, M, k), dtype=torch.int32, device="cuda")
+    B.nanospec_topk_remap(st.h, lg, M, k, oi, None)
+    torch.cuda.synchronize()
+    assert oi.cpu().numpy()[0, 0].tolist() == ctx[:k].tolist()
+    assert oi.cpu().numpy()[0, 1].tolist() == ctx[:k].tolist()
+    st.close()
+
+
+def test_result_independent_of_position_and_run():
+    """the logit of a (W row, H row) pair does not depend on where the row sits in the active list,
+    and two runs give identical bits."""
+    cfg = synth.CONFIGS["c1"]
+    W = host_W(cfg)
+    V, d, M = cfg["V"], cfg["d"], 4
+    H = synth.make_H(cfg, 3, 1, M)[0]
+    dW, dH = dev_bf16(W), dev_bf16(H)
+    st = B.State(V, d, 1, 512, 0, M, 8)
+    cap = st.capacity
+    res = []
+    for ctx in (np.arange(100, 400, dtype=np.int32), np.arange(0, 400, dtype=np.int32), np.arange(100, 400, dtype=np.int32)):
+        B.nanospec_vocab_init(st.h, dev(ctx), [0, len(ctx)], None, [0, 0])
+        lg = torch.empty((1, M, cap), dtype=torch.float32, device="cuda")
+        B.nanospec_sparse_head(st.h, dW, dH, M, lg)
+        torch.cuda.synchronize()
+        res.append(lg.cpu().numpy()[0])
+    assert np.array_equal(res[0][:, :300], res[2][:, :300])
+    assert np.array_equal(res[0][:, :300], res[1][:, 100:400])
+    st.close()
+
+
+def test_argument_errors():
+    L = B.lib()
+    st = _small_state()
+    import ctypes as C
+    assert L.nanospec_create(None, 10, 8, 1, 1, 0, 1, 1) == B.EINVAL
+    h = C.c_void_p()
+    assert L.nanospec_create(C.byref(h), 10, 12, 1, 1, 0, 1, 1) == B.EINVAL        # d % 8 != 0
+    assert L.nanospec_create(C.byref(h), 10, 8, 1, 1, 0, 1, 65) == B.EINVAL        # k_cap > 64
+    assert L.nanospec_create(C.byref(h), 10, 8, 257, 1, 0, 1, 1) == B.EINVAL       # batch > max
+    off_bad = (C.c_int32 * 2)(3, 1)
+    off_ok = (C.c_int32 * 2)(0, 5)
+    assert L.nanospec_vocab_update(st.h, None, off_bad, None, None, None) == B.EINVAL
+    assert L.nanospec_vocab_update(st.h, None, off_ok, None, None, None) == B.EINVAL     # ids missing
+    assert L.nanospec_vocab_init(st.h, None, None, None, None, None) == B.EINVAL
+    buf = torch.zeros(64, dtype=torch.int32, device="cuda")
+    assert L.nanospec_vocab_update(st.h, None, None, buf.data_ptr(), off_ok, None) == B.ECAPACITY  # |T| > topk_cap
+    assert L.nanospec_sparse_head(st.h, buf.data_ptr(), buf.data_ptr(), 4, buf.data_ptr(), None) == B.ECAPACITY
+    assert L.nanospec_sparse_head(st.h, None, buf.data_ptr(), 1, buf.data_ptr(), None) == B.EINVAL
+    assert L.nanospec_topk_remap(st.h, buf.data_ptr(), 1, 65, buf.data_ptr(), None, None) == B.ECAPACITY
+    assert L.nanospec_dense_head(buf.data_ptr(), buf.data_ptr(), 10, 12, 1, buf.data_ptr(), None) == B.EINVAL
+    assert L.nanospec_dense_topk(buf.data_ptr(), 100000, 1, 4, buf.data_ptr(), None, buf.data_ptr(), 8, None) == B.ECAPACITY
+    torch.cuda.synchronize()
+    assert np.array_equal(st.read_active()[0], np.zeros(0, np.int32))               # nothing was enqueued
+    st.close()

@@ -1,0 +1,246 @@
+#!/usr/bin/env python3
+"""Benchmark of the NanoSpec draft-step hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input, with everything
+already resident in HBM:  nanospec_vocab_update (append the accepted tokens, rebuild I)
+-> nanospec_sparse_head (project the draft hidden rows onto W_head[I, :]) -> nanospec_topk_remap.
+The default workload is the Llama-3-8B-shaped head the headline metric is quoted on
+(V=128256, d=4096, |active| ~ 3k, M=8 draft rows, top-10, 1-4 accepted tokens per step).
+
+Cold weights: consecutive draft steps touch almost the same ~24.6 MB of LM-head rows, which would
+sit in the 256 MB Infinity Cache if nothing else ran.  In real decoding the draft backbone and the
+target model stream gigabytes between two head calls, so the benchmark rotates through
+`--replicas` copies of W_head (distinct addresses, same values): every head launch then reads rows
+that have been evicted, and `roofline.achieved` is an HBM number.  `--replicas 1` gives the warm
+figure.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--replicas", type=int, default=16, help="copies of W_head rotated through (1 = warm caches)")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly from Python instead of replaying HIP graphs")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--traffic", default=None, help="HBM bytes per head launch from rocprofv3 --pmc runs (or omit)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1 (the path has no collectives, "
+              "see DESIGN.md for how it would shard)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_26444_amd import binding as B
+    from paper_2605_26444_amd import synth
+
+    torch.cuda.set_device(0)
+    cfg = dict(synth.CONFIGS[args.config])
+    K, Wm = args.steps, args.warmup
+    total_steps = K + Wm
+    cfg["steps"] = total_steps
+    V, d, M, k, Bn = cfg["V"], cfg["d"], cfg["M"], cfg["k"], cfg["batch"]
+    seqs = synth.make_sequences(cfg)
+
+    t0 = time.time()
+    W_host = synth.make_W(cfg)
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    R = max(1, args.replicas)
+    Wd = [to_dev(W_host.view(np.int16)).view(torch.bfloat16)]
+    for _ in range(R - 1):
+        Wd.append(Wd[0].clone())
+    NH = 16                                                   # distinct hidden-state tensors rotated through
+    Hd = [to_dev(synth.make_H(cfg, s).view(np.int16)).view(torch.bfloat16) for s in range(NH)]
+
+    st = B.State(V, d, Bn, seqs["window"], seqs["topk_cap"], M, k)
+    cap = st.capacity
+    logits = torch.empty((Bn, M, cap), dtype=torch.float32, device="cuda")
+    out_ids = torch.empty((Bn, M, k), dtype=torch.int32, device="cuda")
+    out_vals = torch.empty((Bn, M, k), dtype=torch.float32, device="cuda")
+
+    def csr(arrays):
+        off = np.zeros(len(arrays) + 1, np.int32)
+        off[1:] = np.cumsum([len(a) for a in arrays])
+        return np.concatenate(arrays).astype(np.int32), off
+
+    ctx, coff = csr(seqs["ctx"])
+    T0, toff = csr(seqs["T0"])
+    d_ctx, d_T0 = to_dev(ctx), (to_dev(T0) if len(T0) else None)
+    # all appended ids of all steps in one device buffer; per-step host offsets
+    flat, offs, toffs, tflat = [], [], [], []
+    base = 0
+    for s in range(total_steps):
+        f, o = csr(seqs["appends"][s])
+        flat.append(f)
+        offs.append(o + base)
+        base += len(f)
+    d_new = to_dev(np.concatenate(flat))
+    d_T_steps = None
+    if seqs["T_step"][0] is not None:                         # c4: T replaced every step; rotate 8 sets
+        tf = [csr(seqs["T_step"][s]) for s in range(8)]
+        d_T_steps = [(to_dev(f), o) for f, o in tf]
+    use_graph = not args.no_graph
+
+    def step(s, stream):
+        if d_T_steps is not None:
+            tfl, tof = d_T_steps[s % 8]
+            B.nanospec_vocab_update(st.h, d_new, offs[s], tfl, tof, stream)
+        else:
+            B.nanospec_vocab_update(st.h, d_new, offs[s], None, None, stream)
+        B.nanospec_sparse_head(st.h, Wd[s % R], Hd[s % NH], M, logits, stream)
+        B.nanospec_topk_remap(st.h, logits, M, k, out_ids, out_vals, stream)
+
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, first, count):
+        """time fn(i, stream) for i in [first, first+count) on the current stream: the launches are
+        recorded once into a HIP graph (the hot calls never synchronise or allocate, so they can be)
+        and replayed between two events; with --no-graph they are issued eagerly instead."""
+        cur = torch.cuda.current_stream()
+        if use_graph:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                cs = torch.cuda.current_stream().cuda_stream
+                for i in range(first, first + count):
+                    fn(i, cs)
+            torch.cuda.synchronize()
+            e0.record(cur)
+            g.replay()
+            e1.record(cur)
+        else:
+            e0.record(cur)
+            for i in range(first, first + count):
+                fn(i, cur.cuda_stream)
+            e1.record(cur)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1)
+
+    stream = torch.cuda.current_stream().cuda_stream
+    B.nanospec_vocab_init(st.h, d_ctx, coff, d_T0, toff, stream)
+    for s in range(Wm):
+        step(s, stream)
+    torch.cuda.synchronize()
+    ms = timed(step, Wm, K)
+    n_active = [len(a) for a in st.read_active()]
+    n_sum = int(np.sum(n_active))
+
+    # roofline leg: the sparse-head kernel alone, same launch configuration, cold rotation, HIP events
+    # on the launch stream around a back-to-back train of launches (no host work in between).
+    NL = 480
+    head = lambda i, cs: B.nanospec_sparse_head(st.h, Wd[i % R], Hd[i % NH], M, logits, cs)
+    for i in range(32):
+        head(i, stream)
+    torch.cuda.synchronize()
+    head_us = timed(head, 0, NL) * 1e3 / NL
+    alg_bytes = n_sum * d * 2                                  # gathered weight bytes per launch
+    achieved = alg_bytes / (head_us * 1e-6) / 1e9
+
+    # per-call times of the other two steps (informational)
+    def train(fn, n=200):
+        for i in range(4):
+            fn(i, stream)
+        torch.cuda.synchronize()
+        return timed(fn, 0, n) * 1e3 / n
+    zero_off = np.zeros(Bn + 1, np.int32) + offs[0][0]
+    upd_us = train(lambda i, cs: B.nanospec_vocab_update(st.h, d_new, zero_off, None, None, cs))
+    topk_us = train(lambda i, cs: B.nanospec_topk_remap(st.h, logits, M, k, out_ids, out_vals, cs))
+
+    # dense comparison point: full-vocabulary head + top-k over V
+    dense = None
+    if not args.no_dense:
+        Mt = Bn * M
+        dl = torch.empty((Mt, V), dtype=torch.float32, device="cuda")
+        wsb = B.nanospec_dense_topk_workspace(V, Mt, k)
+        ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+        di = torch.empty((Mt, k), dtype=torch.int32, device="cuda")
+        dv = torch.empty((Mt, k), dtype=torch.float32, device="cuda")
+
+        def dstep(i, cs):
+            B.nanospec_dense_head(Wd[i % R], Hd[i % NH], V, d, Mt, dl, cs)
+            B.nanospec_dense_topk(dl, V, Mt, k, di, dv, ws, wsb, cs)
+        dense_us = train(dstep, 40)
+        dense_head_us = train(lambda i, cs: B.nanospec_dense_head(Wd[i % R], Hd[i % NH], V, d, Mt, dl, cs), 40)
+        dense = {"step_us": round(dense_us, 2), "head_us": round(dense_head_us, 2),
+                 "head_GBps": round(V * d * 2 / (dense_head_us * 1e-6) / 1e9, 1),
+                 "speedup_step": round(dense_us / (ms * 1e3 / K), 2),
+                 "speedup_head": round(dense_head_us / head_us, 2)}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, seqs, W_host, synth)
+
+    out = {
+        "metric": "sparse-head draft steps/s + gathered HBM GB/s (V=128256,d=4096,|active|~3k)",
+        "value": round(K / (ms * 1e-3), 1), "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": round(ms / K, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.config}: V={V} d={d} batch={Bn} M={M} k={k} |active|={n_active[0]} "
+                               f"window={seqs['window']} |T|={len(seqs['T0'][0])} accept={cfg['acc']}",
+                   "replicas_of_W": R, "weights": "cold (rotated)" if R > 1 else "warm",
+                   "launch": "hip graph replay" if use_graph else "eager"},
+        "gathered_GBps": round(achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": "nanospec_sparse_head", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": float(args.traffic) if args.traffic else None,
+                     "bytes_per_launch": alg_bytes, "us_per_launch": round(head_us, 3)},
+        "kernels_us": {"vocab_update": round(upd_us, 2), "sparse_head": round(head_us, 2), "topk_remap": round(topk_us, 2)},
+        "dense": dense,
+        "cpu_baseline": cpu,
+        "setup_s": round(time.time() - t0, 1),
+    }
+    print(json.dumps(out))
+    st.close()
+
+
+def cpu_baseline(cfg, seqs, W_host, synth):
+    """The oracle as it stands, timed on this host's cores over a bounded run of the same steps."""
+    import oracle
+    M, k, Bn = cfg["M"], cfg["k"], cfg["batch"]
+    threads = oracle.max_threads()
+    voc = [oracle.Vocab(cfg["V"], seqs["window"]) for _ in range(Bn)]
+    for b in range(Bn):
+        voc[b].init(seqs["ctx"][b], seqs["T0"][b])
+
+    def one(s):
+        Hs = synth.make_H(cfg, s % 16)
+        for b in range(Bn):
+            Ts = seqs["T_step"][s % len(seqs["T_step"])]
+            voc[b].update(seqs["appends"][s % len(seqs["appends"])][b], Ts[b] if Ts is not None else None)
+            act = voc[b].active()
+            z32, _ = oracle.head(W_host, Hs[b], ids=act, want64=False, omp=True)
+            for m in range(M):
+                oracle.topk(z32[m], act, k)
+    t = time.time()
+    one(0)
+    t1 = time.time() - t
+    n = int(min(max(15.0 / max(t1, 1e-3), 3), 5000))
+    t = time.time()
+    for s in range(1, 1 + n):
+        one(s)
+    el = time.time() - t
+    return {"value": round(n / el, 3), "unit": "steps/s", "cores": threads, "kind": "oracle",
+            "sample": f"{n} consecutive steps of the same workload (vocabulary rebuild + fp32 head + full-sort "
+                      f"top-k), OpenMP over active rows, {el:.1f} s"}
+
+
+if __name__ == "__main__":
+    main()

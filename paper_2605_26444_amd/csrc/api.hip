@@ -182,7 +182,7 @@ nanospec_status nanospec_sparse_head(nanospec_state* st, const void* d_W_bf16, c
                                      float* d_logits, void* hip_stream) {
   if (!st || !d_W_bf16 || !d_H_bf16 || !d_logits || M < 1) return NANOSPEC_EINVAL;
   if (M > st->m_cap) return NANOSPEC_ECAPACITY;
-  hipError_t e = launch_head(d_W_bf16, d_H_bf16, st->vp.ids, st->vp.n, 0, st->vp.cap, st->batch, M, st->d, st->vp.cap,
+  hipError_t e = launch_head(d_W_bf16, d_H_bf16, st->vp.ids, st->vp.n, 0, st->vp.cap, st->V, st->batch, M, st->d, st->vp.cap,
                              st->vp.cap, d_logits, st->partial, st->partial_bytes, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;
 }
@@ -199,7 +199,7 @@ nanospec_status nanospec_topk_remap(nanospec_state* st, const float* d_logits, i
 nanospec_status nanospec_dense_head(const void* d_W_bf16, const void* d_H_bf16, int32_t V, int32_t d, int32_t M_total,
                                     float* d_logits, void* hip_stream) {
   if (!d_W_bf16 || !d_H_bf16 || !d_logits || V < 1 || d < 8 || d % 8 != 0 || M_total < 1) return NANOSPEC_EINVAL;
-  hipError_t e = launch_head(d_W_bf16, d_H_bf16, nullptr, nullptr, V, V, 1, M_total, d, V, 0, d_logits, nullptr, 0,
+  hipError_t e = launch_head(d_W_bf16, d_H_bf16, nullptr, nullptr, V, V, V, 1, M_total, d, V, 0, d_logits, nullptr, 0,
                              static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;
 }

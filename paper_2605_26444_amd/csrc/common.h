@@ -56,7 +56,7 @@ hipError_t vocab_configure(nanospec_state* st);
 // head.hip
 // logits[b][m][j] for j < n_b (n read on the device).  ids == nullptr: identity list of n_fixed rows.
 hipError_t launch_head(const void* W, const void* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
-                       int32_t cap_rows, int32_t batch, int32_t M, int32_t d, int64_t ld_logits,
+                       int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld_logits,
                        int64_t ids_stride, float* logits, float* partial, int64_t partial_bytes, hipStream_t s);
 
 // topk.hip

@@ -1,6 +1,8 @@
 // LM-head projection onto a gathered set of rows (paper Sec. 3.1: Eq. 1 restricted to I_t) and onto
 // all rows (Eq. 1, the dense comparison point).  The rows are read straight from W_head inside the
 // projection; no packed copy is made.
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace nanospec {
@@ -64,14 +66,410 @@ __global__ __launch_bounds__(256) void head_generic_kernel(const uint16_t* __res
   }
 }
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Matrix-core kernel.  A workgroup of four wavefronts owns R = 16/P gathered rows; per K-iteration
+// wavefront w streams columns [kb + w*512*P, +512*P) of those rows with fully coalesced 16-byte loads
+// (one instruction = 1 KB of one row), parks them in its private LDS region and reads them back in the
+// operand layout of v_mfma_f32_16x16x32_bf16 (lane = row + 16*kgroup, 8 consecutive k per lane).
+// The hidden rows take the same route as the B operand.  P > 1 folds P column parts of the same rows
+// into the 16 rows of the A tile (and of the same hidden rows into the 16 columns of the B tile), so
+// that with few hidden rows all 16x16x32 operand slots still carry useful data; only the P diagonal
+// RxR blocks of the product are kept.  No wavefront waits for another until the final fixed-order sum
+// of the four K-slices, so results do not depend on the row's position or on run-to-run timing.
+template <int P, int MT>
+__global__ __launch_bounds__(256) void head_mfma_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
+                                                        const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
+                                                        int n_fixed, int V, int M, int d, int64_t ld, int64_t ids_stride,
+                                                        float* __restrict__ logits) {
+  constexpr int R = 16 / P;
+  constexpr int CW = 512 * P;
+  constexpr int STRB = CW * 2 + 16;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int b = blockIdx.z;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int j0 = blockIdx.x * R;
+  char* reg = smem + w * (R * STRB);
+  const uint16_t* Hb = H + (int64_t)b * M * d;
+
+  const int ai = lane & 15, aq = lane >> 4;
+  const int rd_off = (ai % R) * STRB + (ai / R) * 1024 + aq * 16;   // + t*64 per MFMA step
+  const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+
+  // hidden rows of (K-iteration kb, m-tile mt) for this wavefront's column slice
+  auto load_h = [&](int kb, int mt, u32x4(&hv)[16]) {
+    const int c0 = kb + w * CW + lane * 8;
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+      const int c = c0 + (s % P) * 512;
+      const int m = mt * R + s / P;
+      hv[s] = (c < d && m < M) ? *reinterpret_cast<const u32x4*>(Hb + (int64_t)m * d + c) : zero;
+    }
+  };
+  // The first hidden-row loads depend on nothing but the arguments: they go out before the row
+  // count and the row ids have come back.
+  u32x4 hv[16];
+  load_h(0, 0, hv);
+
+  // The row ids are fetched without waiting for the row count: the id list is allocated up to its
+  // capacity, so reading past n is safe, and a stale id is clamped into the matrix (its product is
+  // never stored).  This keeps "count -> ids -> rows" from becoming three dependent round trips.
+  const uint16_t* wrow[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    int64_t row = j0 + r;
+    if (ids) row = ids[b * ids_stride + j0 + r];
+    row = row < 0 ? 0 : (row >= V ? V - 1 : row);
+    wrow[r] = W + row * d;
+  }
+  const int n = n_dev ? n_dev[b] : n_fixed;
+  if (j0 >= n) return;
+
+  f32x4 acc[MT];
+#pragma unroll
+  for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int kb = 0; kb < d; kb += 4 * CW) {
+    const int c0 = kb + w * CW + lane * 8;
+    if (kb + w * CW >= d) continue;                                   // whole slice beyond the row end
+    u32x4 wv[16];
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+      const int c = c0 + (s % P) * 512;
+      wv[s] = (c < d) ? *reinterpret_cast<const u32x4*>(wrow[s / P] + c) : zero;
+    }
+    bf16x8 av[16];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      if (mt * R >= M) break;
+      if (kb != 0 || mt != 0) load_h(kb, mt, hv);
+#pragma unroll
+      for (int s = 0; s < 16; ++s)
+        *reinterpret_cast<u32x4*>(reg + (s / P) * STRB + (s % P) * 1024 + lane * 16) = hv[s];
+      bf16x8 bv[16];
+#pragma unroll
+      for (int t = 0; t < 16; ++t) bv[t] = *reinterpret_cast<const bf16x8*>(reg + rd_off + t * 64);
+      if (mt == 0) {
+#pragma unroll
+        for (int s = 0; s < 16; ++s)
+          *reinterpret_cast<u32x4*>(reg + (s / P) * STRB + (s % P) * 1024 + lane * 16) = wv[s];
+#pragma unroll
+        for (int t = 0; t < 16; ++t) av[t] = *reinterpret_cast<const bf16x8*>(reg + rd_off + t * 64);
+      }
+#pragma unroll
+      for (int t = 0; t < 16; ++t) acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[t], bv[t], acc[mt], 0, 0, 0);
+    }
+  }
+
+  // the four K-slices meet in LDS: every wavefront leaves its 16x16 tiles in its own region
+  float* red = reinterpret_cast<float*>(reg);
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) red[mt * 256 + (aq * 4 + v) * 16 + ai] = acc[mt][v];
+  __syncthreads();
+  constexpr int OUT = R * R;                                           // useful outputs per m-tile
+  for (int o = threadIdx.x; o < OUT * MT; o += 256) {
+    const int mt = o / OUT, r = (o % OUT) / R, mm = o % R;
+    const int m = mt * R + mm;
+    if (j0 + r >= n || m >= M) continue;
+    float s = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < 4; ++ww) {
+      const float* t = reinterpret_cast<const float*>(smem + ww * (R * STRB)) + mt * 256;
+#pragma unroll
+      for (int p = 0; p < P; ++p) s += t[(p * R + r) * 16 + p * R + mm];
+    }
+    logits[((int64_t)b * M + m) * ld + j0 + r] = s;
+  }
+}
+
+// Matrix-core kernel for few hidden rows (M <= 16), no LDS staging at all.
+// The 16 rows of the A tile of v_mfma_f32_16x16x32_bf16 are 4 gathered rows x 4 column parts, the 16
+// columns of the B tile are 4 hidden rows x the same 4 column parts; only the diagonal (part == part)
+// 4x4 blocks of the product are kept and summed.  With operand row i = 4*row + part and the part as
+// the fastest index, the four lanes of a quad read 64 consecutive bytes of one matrix row and one
+// load instruction covers 4 rows x 256 contiguous bytes -- fully coalesced straight into the operand
+// registers, for W_head and for the hidden rows alike.  A dot product does not care in which order
+// its terms are paired up as long as both operands agree, which they do: both use the same map from
+// (lane, step) to column.  The matrix cores run at a quarter of their peak this way, which is still
+// several times the arithmetic the HBM stream can feed.
+// A workgroup of four wavefronts owns 4*RT rows; wavefront w takes columns [kb + w*128*KS, +128*KS)
+// per K-iteration; the four K-slices are summed in fixed order through LDS.
+template <int RT, int MT, int KS, int NW>
+__global__ __launch_bounds__(64 * NW) void head_quad_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
+                                                        const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
+                                                        int n_fixed, int V, int M, int d, int64_t ld, int64_t ids_stride,
+                                                        float* __restrict__ logits) {
+  constexpr int ROWS = 4 * RT;
+  __shared__ float red[NW][RT * MT * 16];
+  const int b = blockIdx.z;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int j0 = blockIdx.x * ROWS;
+  const int orow = (lane & 15) >> 2, part = lane & 3, q = lane >> 4;   // operand row / column part / k group
+  const int coff = w * (128 * KS) + q * 32 + part * 8;                  // + kb + t*128
+  const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+  const uint16_t* Hb = H + (int64_t)b * M * d;
+
+  auto load_h = [&](int kb, u32x4(&hv)[MT][KS]) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = mt * 4 + orow;
+#pragma unroll
+      for (int t = 0; t < KS; ++t) {
+        const int c = kb + coff + t * 128;
+        hv[mt][t] = (c < d && m < M) ? *reinterpret_cast<const u32x4*>(Hb + (int64_t)m * d + c) : zero;
+      }
+    }
+  };
+  // Row ids and the row count come through the scalar cache (uniform addresses), issued before any
+  // vector load so that nothing queues ahead of them.  The ids are read without waiting for the
+  // count: the list is allocated to its capacity, a stale id is clamped into the matrix and its
+  // product is never stored.
+  int idr[ROWS];
+#pragma unroll
+  for (int r = 0; r < ROWS; ++r) idr[r] = ids ? ids[b * ids_stride + j0 + r] : j0 + r;
+  const int n = n_dev ? n_dev[b] : n_fixed;
+  // hidden rows of the first K-iteration depend on the arguments only: they stream in from L2
+  // while the ids are still on their way
+  u32x4 hv[MT][KS];
+  load_h(0, hv);
+
+  const uint16_t* wrow[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    int64_t row = orow == 0 ? idr[rt * 4] : (orow == 1 ? idr[rt * 4 + 1] : (orow == 2 ? idr[rt * 4 + 2] : idr[rt * 4 + 3]));
+    row = row < 0 ? 0 : (row >= V ? V - 1 : row);
+    wrow[rt] = W + row * d;
+  }
+  if (j0 >= n) return;
+
+  f32x4 acc[RT][MT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[rt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int kb = 0; kb < d; kb += NW * 128 * KS) {
+    if (kb + w * (128 * KS) >= d) break;
+    u32x4 wv[RT][KS];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int t = 0; t < KS; ++t) {
+        const int c = kb + coff + t * 128;
+        wv[rt][t] = (c < d) ? *reinterpret_cast<const u32x4*>(wrow[rt] + c) : zero;
+      }
+    if (kb != 0) load_h(kb, hv);
+#pragma unroll
+    for (int t = 0; t < KS; ++t)
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          acc[rt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[rt][t]),
+                                                               __builtin_bit_cast(bf16x8, hv[mt][t]), acc[rt][mt], 0, 0, 0);
+  }
+
+  // result lane l holds product rows 4*(l/16)+v, column l%16: the diagonal block entry is v == l%4;
+  // the four parts sit in the four lanes of a quad
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const f32x4 a = acc[rt][mt];
+      float x = part == 0 ? a[0] : (part == 1 ? a[1] : (part == 2 ? a[2] : a[3]));
+      x += __shfl_xor(x, 1);
+      x += __shfl_xor(x, 2);
+      if (part == 0) red[w][(rt * MT + mt) * 16 + q * 4 + orow] = x;     // (row q of the tile, hidden row orow)
+    }
+  __syncthreads();
+  for (int o = threadIdx.x; o < RT * MT * 16; o += 64 * NW) {
+    const int rt = o / (MT * 16), mt = (o / 16) % MT, r = (o % 16) / 4, mm = o % 4;
+    const int j = j0 + rt * 4 + r, m = mt * 4 + mm;
+    if (j >= n || m >= M) continue;
+    float s = red[0][o];
+#pragma unroll
+    for (int ww = 1; ww < NW; ++ww) s += red[ww][o];
+    logits[((int64_t)b * M + m) * ld + j] = s;
+  }
+}
+
+template <int RT, int MT, int KS, int NW>
+static hipError_t run_quad(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
+                           int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride,
+                           float* logits, hipStream_t s) {
+  dim3 grid((cap_rows + 4 * RT - 1) / (4 * RT), 1, batch);
+  head_quad_kernel<RT, MT, KS, NW><<<grid, 64 * NW, 0, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
+  return hipGetLastError();
+}
+
+// Balanced variant of the quad kernel for small row counts: a fixed grid (one workgroup per compute
+// unit) in which workgroup g owns the 4-row tiles g, g+G, g+2G, ...  All loads of up to TPW tiles are
+// put in flight at once, the hidden rows are fetched once per workgroup, and every compute unit
+// streams (almost) the same number of bytes, so none of them idles while others still wait on HBM.
+template <int MT, int KS, int NW, int TPW>
+__global__ __launch_bounds__(64 * NW) void head_quad_persist_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
+                                                                    const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
+                                                                    int n_fixed, int cap_rows, int V, int M, int d, int64_t ld,
+                                                                    int64_t ids_stride, float* __restrict__ logits) {
+  __shared__ float red[NW][TPW * MT * 16];
+  const int b = blockIdx.z, G = gridDim.x;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int orow = (lane & 15) >> 2, part = lane & 3, q = lane >> 4;
+  const int coff = w * (128 * KS) + q * 32 + part * 8;
+  const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+  const uint16_t* Hb = H + (int64_t)b * M * d;
+  const int cap_tiles = (cap_rows + 3) >> 2;
+  const int n = n_dev ? n_dev[b] : n_fixed;               // only consumed after the id loads are out
+
+  for (int t0 = blockIdx.x; t0 < cap_tiles; t0 += G * TPW) {
+    // row ids of this round's tiles through the scalar cache (uniform addresses), not waiting on n
+    int idr[TPW][4];
+#pragma unroll
+    for (int tp = 0; tp < TPW; ++tp) {
+      const int j = (t0 + tp * G) * 4;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) idr[tp][r] = ids ? ((j + r < cap_rows) ? ids[b * ids_stride + j + r] : 0) : j + r;
+    }
+    f32x4 acc[TPW][MT];
+#pragma unroll
+    for (int tp = 0; tp < TPW; ++tp)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) acc[tp][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    bool any = false;
+    for (int kb = 0; kb < d; kb += NW * 128 * KS) {
+      if (kb + w * (128 * KS) >= d) break;
+      u32x4 hv[MT][KS];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const int m = mt * 4 + orow;
+#pragma unroll
+        for (int t = 0; t < KS; ++t) {
+          const int c = kb + coff + t * 128;
+          hv[mt][t] = (c < d && m < M) ? *reinterpret_cast<const u32x4*>(Hb + (int64_t)m * d + c) : zero;
+        }
+      }
+      if ((t0 << 2) >= n) break;                                           // nothing live in this round
+      any = true;
+      u32x4 wv[TPW][KS];
+#pragma unroll
+      for (int tp = 0; tp < TPW; ++tp) {
+        int64_t row = orow == 0 ? idr[tp][0] : (orow == 1 ? idr[tp][1] : (orow == 2 ? idr[tp][2] : idr[tp][3]));
+        row = row < 0 ? 0 : (row >= V ? V - 1 : row);
+        const uint16_t* wr = W + row * d;
+        const bool live = ((t0 + tp * G) << 2) < n;
+#pragma unroll
+        for (int t = 0; t < KS; ++t) {
+          const int c = kb + coff + t * 128;
+          wv[tp][t] = (live && c < d) ? *reinterpret_cast<const u32x4*>(wr + c) : zero;
+        }
+      }
+#pragma unroll
+      for (int tp = 0; tp < TPW; ++tp)
+#pragma unroll
+        for (int t = 0; t < KS; ++t)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+            acc[tp][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[tp][t]),
+                                                                 __builtin_bit_cast(bf16x8, hv[mt][t]), acc[tp][mt], 0, 0, 0);
+    }
+    if ((t0 << 2) >= n) break;                                             // uniform over the workgroup
+#pragma unroll
+    for (int tp = 0; tp < TPW; ++tp)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const f32x4 a = acc[tp][mt];
+        float x = part == 0 ? a[0] : (part == 1 ? a[1] : (part == 2 ? a[2] : a[3]));
+        x += __shfl_xor(x, 1);
+        x += __shfl_xor(x, 2);
+        if (part == 0) red[w][(tp * MT + mt) * 16 + q * 4 + orow] = any ? x : 0.f;
+      }
+    __syncthreads();
+    for (int o = threadIdx.x; o < TPW * MT * 16; o += 64 * NW) {
+      const int tp = o / (MT * 16), mt = (o / 16) % MT, r = (o % 16) / 4, mm = o % 4;
+      const int j = (t0 + tp * G) * 4 + r, m = mt * 4 + mm;
+      if (j >= n || m >= M) continue;
+      float s = red[0][o];
+#pragma unroll
+      for (int ww = 1; ww < NW; ++ww) s += red[ww][o];
+      logits[((int64_t)b * M + m) * ld + j] = s;
+    }
+    __syncthreads();
+  }
+}
+
+template <int MT, int KS, int NW, int TPW>
+static hipError_t run_quad_persist(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev,
+                                   int32_t n_fixed, int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d,
+                                   int64_t ld, int64_t ids_stride, float* logits, int G, hipStream_t s) {
+  dim3 grid(G, 1, batch);
+  head_quad_persist_kernel<MT, KS, NW, TPW><<<grid, 64 * NW, 0, s>>>(W, H, ids, n_dev, n_fixed, cap_rows, V, M, d, ld,
+                                                                    ids_stride, logits);
+  return hipGetLastError();
+}
+
+template <int P, int MT>
+static hipError_t run_mfma(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
+                           int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride,
+                           float* logits, hipStream_t s) {
+  constexpr int R = 16 / P;
+  constexpr int LDS = 4 * R * (512 * P * 2 + 16);
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_mfma_kernel<P, MT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  dim3 grid((cap_rows + R - 1) / R, 1, batch);
+  head_mfma_kernel<P, MT><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
+  return hipGetLastError();
+}
+
+static int head_variant() {
+  static int v = -1;
+  if (v < 0) {
+    const char* e = getenv("NANOSPEC_HEAD_VARIANT");
+    v = e ? atoi(e) : 0;
+  }
+  return v;
+}
+
 hipError_t launch_head(const void* W, const void* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
-                       int32_t cap_rows, int32_t batch, int32_t M, int32_t d, int64_t ld_logits, int64_t ids_stride,
+                       int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld_logits, int64_t ids_stride,
                        float* logits, float* partial, int64_t partial_bytes, hipStream_t s) {
   (void)partial;
   (void)partial_bytes;
+  const uint16_t* Wp = static_cast<const uint16_t*>(W);
+  const uint16_t* Hp = static_cast<const uint16_t*>(H);
+  const int variant = head_variant();
+  if (variant == 11 && M <= 8) return run_quad<2, 2, 4, 8>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
+  if (variant == 12 && M <= 8) return run_quad<1, 2, 8, 4>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
+  if (variant == 13 && M <= 8) return run_quad<4, 2, 8, 4>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
+  if (variant == 14 && M <= 8) return run_quad<2, 2, 2, 16>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
+  if (variant == 15 && M <= 8) return run_quad<1, 2, 4, 8>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
+  if (variant == 16 && M <= 8) return run_quad<4, 2, 4, 8>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
+  if (variant == 20 && M <= 8) return run_quad_persist<2, 8, 4, 3>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, 256, s);
+  if (variant == 21 && M <= 8) return run_quad_persist<2, 8, 4, 2>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, 512, s);
+  if (variant == 22 && M <= 8) return run_quad_persist<2, 4, 8, 3>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, 256, s);
+  if (variant == 23 && M <= 8) return run_quad_persist<2, 8, 4, 1>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, 768, s);
+  if (variant == 24 && M <= 8) return run_quad_persist<2, 8, 4, 4>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, 256, s);
+  if (variant == 0) {
+    if (M <= 4) return run_quad<2, 1, 8, 4>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
+    if (M <= 8) return run_quad<2, 2, 8, 4>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
+    if (M <= 12) return run_quad<4, 3, 4, 4>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
+    if (M <= 16) return run_quad<4, 4, 4, 4>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
+  }
+  if (variant != 9) {
+    if (M <= 8) return run_mfma<2, 1>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
+    if (M <= 16) return run_mfma<1, 1>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
+    if (M <= 32) return run_mfma<1, 2>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
+    if (M <= 64) return run_mfma<1, 4>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
+  }
   dim3 grid((cap_rows + 3) / 4, 1, batch);
-  head_generic_kernel<8><<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(H), ids,
-                                              n_dev, n_fixed, M, d, ld_logits, ids_stride, logits);
+  head_generic_kernel<8><<<grid, 256, 0, s>>>(Wp, Hp, ids, n_dev, n_fixed, M, d, ld_logits, ids_stride, logits);
   return hipGetLastError();
 }
 

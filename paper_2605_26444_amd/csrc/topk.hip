@@ -2,203 +2,198 @@
 // the k largest logits of every row, ordered by value descending then global id ascending, mapped
 // from the position in the active list back to the global token id.
 //
-// A wavefront finds its k best by k rounds of a shuffle arg-max over per-lane candidates held in
-// registers; the wavefronts' winners meet in LDS and one wavefront repeats the rounds over them.
-// Rows longer than one workgroup's reach are cut into chunks whose winners a second kernel merges.
+// Every lane keeps a run of consecutive logits in registers, so "lower position" means "lower lane,
+// then lower register".  A wavefront extracts its k best in k rounds: a DPP max-reduction of the
+// lane maxima, a ballot of the lanes that hold that maximum (the lowest such lane owns the
+// lowest-position occurrence), one readlane for the register index, and the winner is blanked.
+// The wavefronts' winners meet in LDS in position order and one wavefront repeats the rounds over
+// them.  Rows longer than one workgroup's reach are cut into chunks whose winners a second kernel
+// merges the same way.  Values of -inf mark "nothing left" (logits are finite by contract).
 #include <limits.h>
 
 #include "common.h"
 
 namespace nanospec {
 
-__device__ __forceinline__ bool better(float v1, int i1, float v2, int i2) {
-  return v1 > v2 || (v1 == v2 && i1 < i2);
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_max(float x) {
+  const int ninf = __float_as_int(-INFINITY);
+  const int y = __builtin_amdgcn_update_dpp(ninf, __float_as_int(x), CTRL, ROW_MASK, 0xf, false);
+  return fmaxf(x, __int_as_float(y));
 }
 
-// k rounds over the EPT (value, index) pairs each lane holds; `mask` marks the live ones.
-// Round r's winner is handed to emit(r, value, index) by every lane (index INT_MAX: none left).
+// maximum over the 64 lanes, returned in every lane
+__device__ __forceinline__ float wave_max(float x) {
+  x = dpp_max<0x111, 0xf>(x);   // row_shr:1
+  x = dpp_max<0x112, 0xf>(x);   // row_shr:2
+  x = dpp_max<0x114, 0xf>(x);   // row_shr:4
+  x = dpp_max<0x118, 0xf>(x);   // row_shr:8   -> lane 15 of each row holds the row maximum
+  x = dpp_max<0x142, 0xa>(x);   // row_bcast:15 into rows 1 and 3
+  x = dpp_max<0x143, 0xc>(x);   // row_bcast:31 into rows 2 and 3 -> lane 63 holds the maximum
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+
+// k rounds over the EPT values each lane holds (position = lane*EPT + register index).
+// emit(r, value, position) is called by every lane with wave-uniform arguments; value == -inf
+// means that fewer than r+1 elements exist.
 template <int EPT, typename Emit>
-__device__ __forceinline__ void wave_topk(const float (&val)[EPT], const int (&idx)[EPT], uint32_t mask, int k, Emit emit) {
+__device__ __forceinline__ void wave_select(float (&v)[EPT], int k, int lane, Emit emit) {
   for (int r = 0; r < k; ++r) {
-    float bv = -INFINITY;
-    int bi = INT_MAX, be = -1;
+    float ml = v[0];
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) {
-      if (((mask >> e) & 1u) && better(val[e], idx[e], bv, bi)) {
-        bv = val[e];
-        bi = idx[e];
-        be = e;
-      }
-    }
-    const int mine = bi;
+    for (int e = 1; e < EPT; ++e) ml = fmaxf(ml, v[e]);
+    const float m = wave_max(ml);
+    const unsigned long long ball = __ballot(ml == m);
+    const int L = ball ? __ffsll(ball) - 1 : 0;
+    int ef = 0;
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      const float ov = __shfl_xor(bv, o);
-      const int oi = __shfl_xor(bi, o);
-      if (better(ov, oi, bv, bi)) {
-        bv = ov;
-        bi = oi;
-      }
-    }
-    if (be >= 0 && mine == bi) mask &= ~(1u << be);
-    emit(r, bv, bi);
+    for (int e = EPT - 1; e >= 0; --e) ef = (v[e] == m) ? e : ef;
+    const int eL = __builtin_amdgcn_readlane(ef, L);
+    emit(r, ball ? m : -INFINITY, L * EPT + eL);
+    const bool mine = lane == L;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) v[e] = (mine && e == eL) ? -INFINITY : v[e];
   }
 }
 
-// One workgroup selects the k best of elements [c*CH, (c+1)*CH) of row (b, m), CH = EPT*THREADS.
-// FINAL: write global ids / values; else write (value, position) candidates for the merge kernel.
-template <int EPT, int THREADS, bool FINAL>
-__global__ __launch_bounds__(THREADS) void topk_select_kernel(const float* __restrict__ logits, int64_t ld,
+// One workgroup of NW wavefronts selects the k best of elements [c*CH, (c+1)*CH) of row (b, m),
+// CH = NW*64*EPT.  FINAL: write global ids / values; else (value, position) for the merge kernel.
+template <int EPT, int NW, bool FINAL>
+__global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __restrict__ logits, int64_t ld,
                                                              const int32_t* __restrict__ ids, int64_t ids_stride,
                                                              const int32_t* __restrict__ n_dev, int n_fixed, int M, int k,
                                                              int32_t* __restrict__ out_ids, float* __restrict__ out_vals,
-                                                             float* __restrict__ cand_val, int32_t* __restrict__ cand_idx) {
-  constexpr int NW = THREADS / 64;
-  constexpr int CE = (NW * kMaxK + 63) / 64;
+                                                             float* __restrict__ cand_val, int32_t* __restrict__ cand_pos) {
+  constexpr int E2 = (NW * kMaxK + 63) / 64;
   __shared__ float s_val[NW * kMaxK];
-  __shared__ int s_idx[NW * kMaxK];
+  __shared__ int s_pos[NW * kMaxK];
   const int c = blockIdx.x, m = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = n_dev ? n_dev[b] : n_fixed;
   const int64_t row = (int64_t)b * M + m;
   const float* src = logits + row * ld;
-  const int base = c * (EPT * THREADS);
+  const int p0 = c * (NW * 64 * EPT) + tid * EPT;            // first position of this lane's run
 
-  float val[EPT];
-  int idx[EPT];
-  uint32_t mask = 0;
+  float v[EPT];
+  if ((ld & 3) == 0) {
 #pragma unroll
-  for (int e = 0; e < EPT; ++e) {
-    const int j = base + e * THREADS + tid;
-    idx[e] = j;
-    val[e] = -INFINITY;
-    if (j < n) {
-      val[e] = src[j];
-      mask |= 1u << e;
+    for (int e = 0; e < EPT; e += 4) {
+      float4 x = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+      if (p0 + e < n) x = *reinterpret_cast<const float4*>(src + p0 + e);   // row stride is a multiple of 4
+      v[e] = (p0 + e < n) ? x.x : -INFINITY;
+      v[e + 1] = (p0 + e + 1 < n) ? x.y : -INFINITY;
+      v[e + 2] = (p0 + e + 2 < n) ? x.z : -INFINITY;
+      v[e + 3] = (p0 + e + 3 < n) ? x.w : -INFINITY;
     }
+  } else {
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) v[e] = (p0 + e < n) ? src[p0 + e] : -INFINITY;
   }
-  wave_topk<EPT>(val, idx, mask, k, [&](int r, float v, int i) {
+  const int wbase = c * (NW * 64 * EPT) + wave * (64 * EPT);
+  wave_select<EPT>(v, k, lane, [&](int r, float val, int pos) {
     if (lane == 0) {
-      s_val[wave * k + r] = v;
-      s_idx[wave * k + r] = i;
+      s_val[wave * k + r] = val;
+      s_pos[wave * k + r] = wbase + pos;
     }
   });
   __syncthreads();
   if (wave != 0) return;
-  float cv[CE];
-  int ci[CE];
-  uint32_t cm = 0;
+  float v2[E2];
 #pragma unroll
-  for (int e = 0; e < CE; ++e) {
-    const int q = e * 64 + lane;
-    cv[e] = -INFINITY;
-    ci[e] = INT_MAX;
-    if (q < NW * k && s_idx[q] != INT_MAX) {
-      cv[e] = s_val[q];
-      ci[e] = s_idx[q];
-      cm |= 1u << e;
-    }
+  for (int e = 0; e < E2; ++e) {
+    const int q = lane * E2 + e;
+    v2[e] = (q < NW * k) ? s_val[q] : -INFINITY;
   }
-  wave_topk<CE>(cv, ci, cm, k, [&](int r, float v, int i) {
-    if (lane == 0) {
-      if (FINAL) {
-        const int64_t o = row * k + r;
-        out_ids[o] = (i == INT_MAX) ? -1 : (ids ? ids[b * ids_stride + i] : i);
-        if (out_vals) out_vals[o] = (i == INT_MAX) ? -INFINITY : v;
-      } else {
-        const int64_t o = (row * gridDim.x + c) * k + r;
-        cand_val[o] = v;
-        cand_idx[o] = (i == INT_MAX) ? -1 : i;
-      }
+  // lane r keeps the r-th winner; ids are looked up and stored by k lanes at once afterwards, so the
+  // dependent id loads overlap instead of costing one round trip per rank
+  float wval = -INFINITY;
+  int wq = 0;
+  wave_select<E2>(v2, k, lane, [&](int r, float val, int q) {
+    if (lane == r) {
+      wval = val;
+      wq = q;
     }
   });
+  if (lane < k) {
+    const bool none = (wval == -INFINITY);
+    const int pos = none ? -1 : s_pos[wq];
+    if (FINAL) {
+      const int64_t o = row * k + lane;
+      out_ids[o] = none ? -1 : (ids ? ids[b * ids_stride + pos] : pos);
+      if (out_vals) out_vals[o] = wval;
+    } else {
+      const int64_t o = (row * gridDim.x + c) * k + lane;
+      cand_val[o] = wval;
+      cand_pos[o] = pos;
+    }
+  }
 }
 
-// Merge the per-chunk winners of one row: at most nchunks*k <= 1024 candidates, 256 threads.
-__global__ __launch_bounds__(256) void topk_merge_kernel(const float* __restrict__ cand_val, const int32_t* __restrict__ cand_idx,
-                                                         int nchunks, const int32_t* __restrict__ ids, int64_t ids_stride,
-                                                         int M, int k, int32_t* __restrict__ out_ids,
-                                                         float* __restrict__ out_vals) {
-  constexpr int NW = 4, EPT = 4, CE = (NW * kMaxK + 63) / 64;
-  __shared__ float s_val[NW * kMaxK];
-  __shared__ int s_idx[NW * kMaxK];
-  const int m = blockIdx.y, b = blockIdx.z;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+// Merge the per-chunk winners of one row (nchunks*k <= 1024 candidates, in position order).
+__global__ __launch_bounds__(64) void topk_merge_kernel(const float* __restrict__ cand_val, const int32_t* __restrict__ cand_pos,
+                                                        int nchunks, const int32_t* __restrict__ ids, int64_t ids_stride,
+                                                        int M, int k, int32_t* __restrict__ out_ids,
+                                                        float* __restrict__ out_vals) {
+  constexpr int EPT = 16;
+  const int m = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
   const int64_t row = (int64_t)b * M + m;
   const int total = nchunks * k;
-  float val[EPT];
-  int idx[EPT];
-  uint32_t mask = 0;
+  const float* cv = cand_val + row * total;
+  const int32_t* cp = cand_pos + row * total;
+  float v[EPT];
 #pragma unroll
   for (int e = 0; e < EPT; ++e) {
-    const int q = e * 256 + tid;
-    val[e] = -INFINITY;
-    idx[e] = INT_MAX;
-    if (q < total) {
-      const int i = cand_idx[row * total + q];
-      if (i >= 0) {
-        val[e] = cand_val[row * total + q];
-        idx[e] = i;
-        mask |= 1u << e;
-      }
-    }
+    const int q = lane * EPT + e;
+    v[e] = (q < total) ? cv[q] : -INFINITY;
   }
-  wave_topk<EPT>(val, idx, mask, k, [&](int r, float v, int i) {
-    if (lane == 0) {
-      s_val[wave * k + r] = v;
-      s_idx[wave * k + r] = i;
+  float wval = -INFINITY;
+  int wq = 0;
+  wave_select<EPT>(v, k, lane, [&](int r, float val, int q) {
+    if (lane == r) {
+      wval = val;
+      wq = q;
     }
   });
-  __syncthreads();
-  if (wave != 0) return;
-  float cv[CE];
-  int ci[CE];
-  uint32_t cm = 0;
-#pragma unroll
-  for (int e = 0; e < CE; ++e) {
-    const int q = e * 64 + lane;
-    cv[e] = -INFINITY;
-    ci[e] = INT_MAX;
-    if (q < NW * k && s_idx[q] != INT_MAX) {
-      cv[e] = s_val[q];
-      ci[e] = s_idx[q];
-      cm |= 1u << e;
-    }
+  if (lane < k) {
+    const bool none = (wval == -INFINITY);
+    const int pos = none ? -1 : cp[wq];
+    const int64_t o = row * k + lane;
+    out_ids[o] = none ? -1 : (ids ? ids[b * ids_stride + pos] : pos);
+    if (out_vals) out_vals[o] = wval;
   }
-  wave_topk<CE>(cv, ci, cm, k, [&](int r, float v, int i) {
-    if (lane == 0) {
-      const int64_t o = row * k + r;
-      out_ids[o] = (i == INT_MAX) ? -1 : (ids ? ids[b * ids_stride + i] : i);
-      if (out_vals) out_vals[o] = (i == INT_MAX) ? -INFINITY : v;
-    }
-  });
 }
 
 static int chunks_for(int32_t cap) { return (cap + kTopkChunk - 1) / kTopkChunk; }
 
 int64_t topk_workspace_bytes(int32_t cap, int32_t rows, int32_t k) {
-  if (cap <= 4096) return 0;
+  if (cap <= kTopkChunk) return 0;
   return (int64_t)rows * chunks_for(cap) * k * 8;
 }
 
 hipError_t launch_topk(const float* logits, int64_t ld, const int32_t* ids, int64_t ids_stride, const int32_t* n_dev,
                        int32_t n_fixed, int32_t cap, int32_t batch, int32_t M, int32_t k, int32_t* out_ids,
                        float* out_vals, char* ws, int64_t ws_bytes, hipStream_t s) {
+  const dim3 rows(1, M, batch);
   if (cap <= 4096) {
-    topk_select_kernel<4, 1024, true><<<dim3(1, M, batch), 1024, 0, s>>>(logits, ld, ids, ids_stride, n_dev, n_fixed, M, k,
-                                                                       out_ids, out_vals, nullptr, nullptr);
+    topk_select_kernel<16, 4, true><<<rows, 256, 0, s>>>(logits, ld, ids, ids_stride, n_dev, n_fixed, M, k, out_ids, out_vals,
+                                                       nullptr, nullptr);
+    return hipGetLastError();
+  }
+  if (cap <= kTopkChunk) {
+    topk_select_kernel<16, 16, true><<<rows, 1024, 0, s>>>(logits, ld, ids, ids_stride, n_dev, n_fixed, M, k, out_ids,
+                                                         out_vals, nullptr, nullptr);
     return hipGetLastError();
   }
   const int nch = chunks_for(cap);
   const int64_t need = topk_workspace_bytes(cap, batch * M, k);
   if (nch * k > 1024 || ws == nullptr || ws_bytes < need) return hipErrorInvalidValue;
   float* cv = reinterpret_cast<float*>(ws);
-  int32_t* ci = reinterpret_cast<int32_t*>(ws + need / 2);
-  topk_select_kernel<16, 1024, false><<<dim3(nch, M, batch), 1024, 0, s>>>(logits, ld, ids, ids_stride, n_dev, n_fixed, M,
-                                                                         k, nullptr, nullptr, cv, ci);
+  int32_t* cp = reinterpret_cast<int32_t*>(ws + need / 2);
+  topk_select_kernel<16, 16, false><<<dim3(nch, M, batch), 1024, 0, s>>>(logits, ld, ids, ids_stride, n_dev, n_fixed, M, k,
+                                                                       nullptr, nullptr, cv, cp);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  topk_merge_kernel<<<dim3(1, M, batch), 256, 0, s>>>(cv, ci, nch, ids, ids_stride, M, k, out_ids, out_vals);
+  topk_merge_kernel<<<rows, 64, 0, s>>>(cv, cp, nch, ids, ids_stride, M, k, out_ids, out_vals);
   return hipGetLastError();
 }
 

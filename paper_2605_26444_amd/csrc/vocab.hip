@@ -5,9 +5,10 @@
 // token id (how many times it occurs inside the window), a window bitmap (counter > 0), a bitmap of
 // the extra candidate set T, and the compacted ascending id list I with its count.  One workgroup
 // per sequence applies an update in ONE launch: counters are adjusted with atomics for every id that
-// leaves or enters the window, bits are fixed only after all counter updates have landed (so an id
-// that is evicted and re-appended in the same call ends up correct), and the union bitmap is
-// compacted with popcounts and a workgroup prefix scan.  Both bitmaps live in LDS during the kernel.
+// leaves or enters the window; the decrement that reaches zero clears the bit and, after a barrier,
+// every entering id sets it (so an id that is evicted and re-appended in the same call ends up
+// correct whatever order the atomics landed in), and the union bitmap is compacted with popcounts
+// and a workgroup prefix scan.  Both bitmaps live in LDS during the kernel.
 #include "common.h"
 
 namespace nanospec {
@@ -70,35 +71,35 @@ __global__ __launch_bounds__(kVocabThreads) void vocab_apply_kernel(VocabPtrs p,
   if (oldest < 0) oldest += W;
   int bad = 0;
 
-  // counters: -1 for every id leaving the window, +1 for every id entering it
-  for (int i = tid; i < n_evict; i += kVocabThreads) {
-    int slot = oldest + i;
-    if (slot >= W) slot -= W;
-    const int e = ring[slot];
-    if (e >= 0) atomicSub(&cnt[e], 1u);
-  }
-  for (int i = tid; i < skip; i += kVocabThreads) bad |= ((unsigned)src[i] >= (unsigned)V);
-  for (int i = tid; i < ae; i += kVocabThreads) {
-    const int v = src[skip + i];
-    if ((unsigned)v < (unsigned)V) atomicAdd(&cnt[v], 1u);
-    else bad = 1;
-  }
-  __threadfence();
-  __syncthreads();
-
-  // bits: window bit = (counter > 0), decided only now that every +1/-1 has landed
+  // Leaving ids first: -1 on the counter with a returning atomic; the decrement that brings a
+  // counter to zero (whichever thread performs it) clears the window bit.  Entering ids get their +1
+  // without waiting for the result: they are inside the window afterwards whatever the order of the
+  // two atomics was, so their bit is simply set -- after the barrier, so that a clear of the same id
+  // by the eviction pass cannot come last.
   for (int i = tid; i < n_evict; i += kVocabThreads) {
     int slot = oldest + i;
     if (slot >= W) slot -= W;
     const int e = ring[slot];
     if (e >= 0) {
-      const uint32_t c = __hip_atomic_load(&cnt[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (c == 0u) atomicAnd(&wb[e >> 5], ~(1u << (e & 31)));
+      const uint32_t old = atomicSub(&cnt[e], 1u);
+      if (old == 1u) atomicAnd(&wb[e >> 5], ~(1u << (e & 31)));
     }
   }
+  for (int i = tid; i < skip; i += kVocabThreads) bad |= ((unsigned)src[i] >= (unsigned)V);
+  __syncthreads();   // every ring slot about to be overwritten has been read, every clear is done
+
   for (int i = tid; i < ae; i += kVocabThreads) {
     const int v = src[skip + i];
-    if ((unsigned)v < (unsigned)V) atomicOr(&wb[v >> 5], 1u << (v & 31));
+    const bool ok = (unsigned)v < (unsigned)V;
+    if (ok) {
+      atomicAdd(&cnt[v], 1u);
+      atomicOr(&wb[v >> 5], 1u << (v & 31));
+    } else {
+      bad = 1;
+    }
+    int slot = pos + i;
+    if (slot >= W) slot -= W;
+    ring[slot] = ok ? v : -1;
   }
   if (replace_T) {
     const int nt = toff.v[b + 1] - toff.v[b];
@@ -110,14 +111,6 @@ __global__ __launch_bounds__(kVocabThreads) void vocab_apply_kernel(VocabPtrs p,
     }
   }
   __syncthreads();
-
-  // ring: the new ids overwrite the slots of the evicted ones (read above, before this barrier)
-  for (int i = tid; i < ae; i += kVocabThreads) {
-    int slot = pos + i;
-    if (slot >= W) slot -= W;
-    const int v = src[skip + i];
-    ring[slot] = ((unsigned)v < (unsigned)V) ? v : -1;
-  }
 
   // compaction of (window | T): popcount per thread, workgroup exclusive scan, ascending emission
   const int wpt = (((nwords + kVocabThreads - 1) / kVocabThreads) + 3) & ~3;

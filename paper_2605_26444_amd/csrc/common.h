@@ -11,6 +11,7 @@ constexpr int kVocabThreads = 1024;   // one workgroup per sequence in the vocab
 constexpr int kTopkThreads = 1024;    // single-pass top-k workgroup
 constexpr int kTopkChunk = 16384;     // elements per workgroup in the two-pass top-k
 constexpr int kMaxK = 64;
+constexpr int kCandMax = 256;          // top-k fast path: most candidates ranked directly
 
 // Per-sequence offsets travel by value in the kernel argument block (no H2D copy, graph-safe).
 struct Offsets {

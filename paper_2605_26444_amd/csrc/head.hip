@@ -197,7 +197,7 @@ __global__ __launch_bounds__(256) void head_mfma_kernel(const uint16_t* __restri
 // several times the arithmetic the HBM stream can feed.
 // A workgroup of four wavefronts owns 4*RT rows; wavefront w takes columns [kb + w*128*KS, +128*KS)
 // per K-iteration; the four K-slices are summed in fixed order through LDS.
-template <int RT, int MT, int KS, int NW>
+template <int RT, int MT, int KS, int NW, bool HFIRST = true, bool NT = false>
 __global__ __launch_bounds__(64 * NW) void head_quad_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
                                                         const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
                                                         int n_fixed, int V, int M, int d, int64_t ld, int64_t ids_stride,
@@ -234,7 +234,7 @@ __global__ __launch_bounds__(64 * NW) void head_quad_kernel(const uint16_t* __re
   // hidden rows of the first K-iteration depend on the arguments only: they stream in from L2
   // while the ids are still on their way
   u32x4 hv[MT][KS];
-  load_h(0, hv);
+  if (HFIRST) load_h(0, hv);
 
   const uint16_t* wrow[RT];
 #pragma unroll
@@ -259,9 +259,11 @@ __global__ __launch_bounds__(64 * NW) void head_quad_kernel(const uint16_t* __re
 #pragma unroll
       for (int t = 0; t < KS; ++t) {
         const int c = kb + coff + t * 128;
-        wv[rt][t] = (c < d) ? *reinterpret_cast<const u32x4*>(wrow[rt] + c) : zero;
+        wv[rt][t] = (c < d) ? (NT ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wrow[rt] + c))
+                                  : *reinterpret_cast<const u32x4*>(wrow[rt] + c))
+                            : zero;
       }
-    if (kb != 0) load_h(kb, hv);
+    if (kb != 0 || !HFIRST) load_h(kb, hv);
 #pragma unroll
     for (int t = 0; t < KS; ++t)
 #pragma unroll
@@ -296,12 +298,12 @@ __global__ __launch_bounds__(64 * NW) void head_quad_kernel(const uint16_t* __re
   }
 }
 
-template <int RT, int MT, int KS, int NW>
+template <int RT, int MT, int KS, int NW, bool HFIRST = true, bool NT = false>
 static hipError_t run_quad(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
                            int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride,
                            float* logits, hipStream_t s) {
   dim3 grid((cap_rows + 4 * RT - 1) / (4 * RT), 1, batch);
-  head_quad_kernel<RT, MT, KS, NW><<<grid, 64 * NW, 0, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
+  head_quad_kernel<RT, MT, KS, NW, HFIRST, NT><<<grid, 64 * NW, 0, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
   return hipGetLastError();
 }
 
@@ -456,6 +458,8 @@ hipError_t launch_head(const void* W, const void* H, const int32_t* ids, const i
   if (variant == 22 && M <= 8) return run_quad_persist<2, 4, 8, 3>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, 256, s);
   if (variant == 23 && M <= 8) return run_quad_persist<2, 8, 4, 1>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, 768, s);
   if (variant == 24 && M <= 8) return run_quad_persist<2, 8, 4, 4>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, 256, s);
+  if (variant == 30 && M <= 8) return run_quad<2, 2, 8, 4, false>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
+  if (variant == 31 && M <= 8) return run_quad<2, 2, 8, 4, true, true>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
   if (variant == 0) {
     if (M <= 4) return run_quad<2, 1, 8, 4>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
     if (M <= 8) return run_quad<2, 2, 8, 4>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);

@@ -9,6 +9,12 @@
 // The wavefronts' winners meet in LDS in position order and one wavefront repeats the rounds over
 // them.  Rows longer than one workgroup's reach are cut into chunks whose winners a second kernel
 // merges the same way.  Values of -inf mark "nothing left" (logits are finite by contract).
+//
+// Fast path in front of the rounds: the k-th largest lane maximum of any one wavefront is a lower
+// bound T on the row's k-th largest value (k lanes of that wavefront hold something >= T), so only
+// elements >= T can be winners.  They are compacted in position order into LDS (typically a few
+// dozen), every thread ranks one candidate against all others, and rank r < k is output slot r.
+// If more than kCandMax elements survive (heavy ties) the kernel falls back to the rounds.
 #include <limits.h>
 
 #include "common.h"
@@ -89,6 +95,85 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
 #pragma unroll
     for (int e = 0; e < EPT; ++e) v[e] = (p0 + e < n) ? src[p0 + e] : -INFINITY;
   }
+  // ---- fast path: threshold from lane maxima, compaction, ranking
+  {
+    __shared__ float s_thr[NW];
+    __shared__ int s_cnt[NW];
+    __shared__ float s_cv[kCandMax];
+    __shared__ int s_cp[kCandMax];
+    float ml = v[0];
+#pragma unroll
+    for (int e = 1; e < EPT; ++e) ml = fmaxf(ml, v[e]);
+    float x = ml, thr = -INFINITY;
+    for (int r = 0; r < k; ++r) {
+      thr = wave_max(x);
+      const unsigned long long ball = __ballot(x == thr);
+      const int L = ball ? __ffsll(ball) - 1 : 0;
+      if (lane == L) x = -INFINITY;
+    }
+    if (lane == 0) s_thr[wave] = thr;
+    __syncthreads();
+    float T = s_thr[0];
+#pragma unroll
+    for (int ww = 1; ww < NW; ++ww) T = fmaxf(T, s_thr[ww]);
+    uint32_t flags = 0;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) flags |= (uint32_t)((p0 + e < n) && (v[e] >= T)) << e;
+    const int mine = __popc(flags);
+    int incl = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int y = __shfl_up(incl, o);
+      if (lane >= o) incl += y;
+    }
+    if (lane == 63) s_cnt[wave] = incl;
+    __syncthreads();
+    int off = incl - mine, C = 0;
+#pragma unroll
+    for (int ww = 0; ww < NW; ++ww) {
+      const int t = s_cnt[ww];
+      if (ww < wave) off += t;
+      C += t;
+    }
+    if (C <= kCandMax) {                                  // uniform over the workgroup
+#pragma unroll
+      for (int e = 0; e < EPT; ++e)
+        if ((flags >> e) & 1u) {
+          s_cv[off] = v[e];
+          s_cp[off] = p0 + e;
+          ++off;
+        }
+      __syncthreads();
+      for (int t = tid; t < (C > k ? C : k); t += 64 * NW) {
+        int64_t o;
+        int pos = -1;
+        float val = -INFINITY;
+        int rank = t;                                       // padding slots when fewer than k exist
+        if (t < C) {
+          val = s_cv[t];
+          pos = s_cp[t];
+          rank = 0;
+          for (int q = 0; q < C; ++q) {
+            const float ov = s_cv[q];
+            rank += (ov > val || (ov == val && q < t)) ? 1 : 0;   // list order is position order
+          }
+        }
+        if (rank < k) {
+          if (FINAL) {
+            o = row * k + rank;
+            out_ids[o] = pos < 0 ? -1 : (ids ? ids[b * ids_stride + pos] : pos);
+            if (out_vals) out_vals[o] = val;
+          } else {
+            o = (row * gridDim.x + c) * k + rank;
+            cand_val[o] = val;
+            cand_pos[o] = pos;
+          }
+        }
+      }
+      return;
+    }
+  }
+  // ---- general path: k rounds per wavefront, then over the wavefronts' winners
   const int wbase = c * (NW * 64 * EPT) + wave * (64 * EPT);
   wave_select<EPT>(v, k, lane, [&](int r, float val, int pos) {
     if (lane == 0) {

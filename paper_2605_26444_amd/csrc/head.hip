@@ -1,8 +1,6 @@
 // LM-head projection onto a gathered set of rows (paper Sec. 3.1: Eq. 1 restricted to I_t) and onto
 // all rows (Eq. 1, the dense comparison point).  The rows are read straight from W_head inside the
 // projection; no packed copy is made.
-#include <stdlib.h>
-
 #include "common.h"
 
 namespace nanospec {
@@ -197,7 +195,7 @@ __global__ __launch_bounds__(256) void head_mfma_kernel(const uint16_t* __restri
 // several times the arithmetic the HBM stream can feed.
 // A workgroup of four wavefronts owns 4*RT rows; wavefront w takes columns [kb + w*128*KS, +128*KS)
 // per K-iteration; the four K-slices are summed in fixed order through LDS.
-template <int RT, int MT, int KS, int NW, bool HFIRST = true, bool NT = false>
+template <int RT, int MT, int KS, int NW>
 __global__ __launch_bounds__(64 * NW) void head_quad_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
                                                         const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
                                                         int n_fixed, int V, int M, int d, int64_t ld, int64_t ids_stride,
@@ -234,7 +232,7 @@ __global__ __launch_bounds__(64 * NW) void head_quad_kernel(const uint16_t* __re
   // hidden rows of the first K-iteration depend on the arguments only: they stream in from L2
   // while the ids are still on their way
   u32x4 hv[MT][KS];
-  if (HFIRST) load_h(0, hv);
+  load_h(0, hv);
 
   const uint16_t* wrow[RT];
 #pragma unroll
@@ -259,11 +257,9 @@ __global__ __launch_bounds__(64 * NW) void head_quad_kernel(const uint16_t* __re
 #pragma unroll
       for (int t = 0; t < KS; ++t) {
         const int c = kb + coff + t * 128;
-        wv[rt][t] = (c < d) ? (NT ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wrow[rt] + c))
-                                  : *reinterpret_cast<const u32x4*>(wrow[rt] + c))
-                            : zero;
+        wv[rt][t] = (c < d) ? *reinterpret_cast<const u32x4*>(wrow[rt] + c) : zero;
       }
-    if (kb != 0 || !HFIRST) load_h(kb, hv);
+    if (kb != 0) load_h(kb, hv);
 #pragma unroll
     for (int t = 0; t < KS; ++t)
 #pragma unroll
@@ -298,117 +294,12 @@ __global__ __launch_bounds__(64 * NW) void head_quad_kernel(const uint16_t* __re
   }
 }
 
-template <int RT, int MT, int KS, int NW, bool HFIRST = true, bool NT = false>
+template <int RT, int MT, int KS, int NW>
 static hipError_t run_quad(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
                            int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride,
                            float* logits, hipStream_t s) {
   dim3 grid((cap_rows + 4 * RT - 1) / (4 * RT), 1, batch);
-  head_quad_kernel<RT, MT, KS, NW, HFIRST, NT><<<grid, 64 * NW, 0, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
-  return hipGetLastError();
-}
-
-// Balanced variant of the quad kernel for small row counts: a fixed grid (one workgroup per compute
-// unit) in which workgroup g owns the 4-row tiles g, g+G, g+2G, ...  All loads of up to TPW tiles are
-// put in flight at once, the hidden rows are fetched once per workgroup, and every compute unit
-// streams (almost) the same number of bytes, so none of them idles while others still wait on HBM.
-template <int MT, int KS, int NW, int TPW>
-__global__ __launch_bounds__(64 * NW) void head_quad_persist_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
-                                                                    const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
-                                                                    int n_fixed, int cap_rows, int V, int M, int d, int64_t ld,
-                                                                    int64_t ids_stride, float* __restrict__ logits) {
-  __shared__ float red[NW][TPW * MT * 16];
-  const int b = blockIdx.z, G = gridDim.x;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int orow = (lane & 15) >> 2, part = lane & 3, q = lane >> 4;
-  const int coff = w * (128 * KS) + q * 32 + part * 8;
-  const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
-  const uint16_t* Hb = H + (int64_t)b * M * d;
-  const int cap_tiles = (cap_rows + 3) >> 2;
-  const int n = n_dev ? n_dev[b] : n_fixed;               // only consumed after the id loads are out
-
-  for (int t0 = blockIdx.x; t0 < cap_tiles; t0 += G * TPW) {
-    // row ids of this round's tiles through the scalar cache (uniform addresses), not waiting on n
-    int idr[TPW][4];
-#pragma unroll
-    for (int tp = 0; tp < TPW; ++tp) {
-      const int j = (t0 + tp * G) * 4;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) idr[tp][r] = ids ? ((j + r < cap_rows) ? ids[b * ids_stride + j + r] : 0) : j + r;
-    }
-    f32x4 acc[TPW][MT];
-#pragma unroll
-    for (int tp = 0; tp < TPW; ++tp)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) acc[tp][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    bool any = false;
-    for (int kb = 0; kb < d; kb += NW * 128 * KS) {
-      if (kb + w * (128 * KS) >= d) break;
-      u32x4 hv[MT][KS];
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const int m = mt * 4 + orow;
-#pragma unroll
-        for (int t = 0; t < KS; ++t) {
-          const int c = kb + coff + t * 128;
-          hv[mt][t] = (c < d && m < M) ? *reinterpret_cast<const u32x4*>(Hb + (int64_t)m * d + c) : zero;
-        }
-      }
-      if ((t0 << 2) >= n) break;                                           // nothing live in this round
-      any = true;
-      u32x4 wv[TPW][KS];
-#pragma unroll
-      for (int tp = 0; tp < TPW; ++tp) {
-        int64_t row = orow == 0 ? idr[tp][0] : (orow == 1 ? idr[tp][1] : (orow == 2 ? idr[tp][2] : idr[tp][3]));
-        row = row < 0 ? 0 : (row >= V ? V - 1 : row);
-        const uint16_t* wr = W + row * d;
-        const bool live = ((t0 + tp * G) << 2) < n;
-#pragma unroll
-        for (int t = 0; t < KS; ++t) {
-          const int c = kb + coff + t * 128;
-          wv[tp][t] = (live && c < d) ? *reinterpret_cast<const u32x4*>(wr + c) : zero;
-        }
-      }
-#pragma unroll
-      for (int tp = 0; tp < TPW; ++tp)
-#pragma unroll
-        for (int t = 0; t < KS; ++t)
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt)
-            acc[tp][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[tp][t]),
-                                                                 __builtin_bit_cast(bf16x8, hv[mt][t]), acc[tp][mt], 0, 0, 0);
-    }
-    if ((t0 << 2) >= n) break;                                             // uniform over the workgroup
-#pragma unroll
-    for (int tp = 0; tp < TPW; ++tp)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const f32x4 a = acc[tp][mt];
-        float x = part == 0 ? a[0] : (part == 1 ? a[1] : (part == 2 ? a[2] : a[3]));
-        x += __shfl_xor(x, 1);
-        x += __shfl_xor(x, 2);
-        if (part == 0) red[w][(tp * MT + mt) * 16 + q * 4 + orow] = any ? x : 0.f;
-      }
-    __syncthreads();
-    for (int o = threadIdx.x; o < TPW * MT * 16; o += 64 * NW) {
-      const int tp = o / (MT * 16), mt = (o / 16) % MT, r = (o % 16) / 4, mm = o % 4;
-      const int j = (t0 + tp * G) * 4 + r, m = mt * 4 + mm;
-      if (j >= n || m >= M) continue;
-      float s = red[0][o];
-#pragma unroll
-      for (int ww = 1; ww < NW; ++ww) s += red[ww][o];
-      logits[((int64_t)b * M + m) * ld + j] = s;
-    }
-    __syncthreads();
-  }
-}
-
-template <int MT, int KS, int NW, int TPW>
-static hipError_t run_quad_persist(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev,
-                                   int32_t n_fixed, int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d,
-                                   int64_t ld, int64_t ids_stride, float* logits, int G, hipStream_t s) {
-  dim3 grid(G, 1, batch);
-  head_quad_persist_kernel<MT, KS, NW, TPW><<<grid, 64 * NW, 0, s>>>(W, H, ids, n_dev, n_fixed, cap_rows, V, M, d, ld,
-                                                                    ids_stride, logits);
+  head_quad_kernel<RT, MT, KS, NW><<<grid, 64 * NW, 0, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
   return hipGetLastError();
 }
 
@@ -430,47 +321,143 @@ static hipError_t run_mfma(const uint16_t* W, const uint16_t* H, const int32_t* 
   return hipGetLastError();
 }
 
-static int head_variant() {
-  static int v = -1;
-  if (v < 0) {
-    const char* e = getenv("NANOSPEC_HEAD_VARIANT");
-    v = e ? atoi(e) : 0;
+// Split-K matrix-core kernel for wide draft trees (16 < M <= 64) on few rows.  A workgroup owns 64
+// gathered rows (one 16-row tile per wavefront) and ONE 512-column slice of K, so that the hidden
+// rows it needs (M x 512) are as many bytes as the weights it streams (64 x 512) instead of four
+// times as many, and enough workgroups exist to fill the chip.  Weights and hidden rows are loaded
+// with coalesced 1 KB-per-row instructions, parked in padded LDS and read back in the operand layout
+// of v_mfma_f32_16x16x32_bf16; the hidden-row slice is shared by the four wavefronts.  Each slice
+// writes its partial products to its own plane; head_splitk_reduce_kernel adds the planes in slice
+// order, so the result is deterministic.
+template <int MT>
+__global__ __launch_bounds__(256) void head_splitk_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
+                                                          const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
+                                                          int V, int M, int d, int cap, int64_t ids_stride,
+                                                          float* __restrict__ partial) {
+  constexpr int STRB = 1024 + 16;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int b = blockIdx.z, sl = blockIdx.y, batch = gridDim.z;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int j0 = blockIdx.x * 64 + w * 16;
+  const int c = sl * 512 + lane * 8;
+  const bool cok = c < d;
+  const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+  char* reg = smem + w * (16 * STRB);
+
+  int idr[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) idr[r] = ids[b * ids_stride + j0 + r];     // scalar loads, capacity-bounded
+  const int n = n_dev[b];
+  u32x4 hv[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int m = w * 16 + r;
+    hv[r] = (cok && m < M) ? *reinterpret_cast<const u32x4*>(H + ((int64_t)b * M + m) * d + c) : zero;
   }
-  return v;
+  if ((int)blockIdx.x * 64 >= n) return;
+  u32x4 wv[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    int64_t row = idr[r];
+    row = row < 0 ? 0 : (row >= V ? V - 1 : row);
+    wv[r] = (cok && j0 + r < n) ? *reinterpret_cast<const u32x4*>(W + row * d + c) : zero;
+  }
+  const int rd_off = (lane & 15) * STRB + (lane >> 4) * 16;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) *reinterpret_cast<u32x4*>(reg + r * STRB + lane * 16) = wv[r];
+  bf16x8 av[16];
+#pragma unroll
+  for (int t = 0; t < 16; ++t) av[t] = *reinterpret_cast<const bf16x8*>(reg + rd_off + t * 64);
+#pragma unroll
+  for (int r = 0; r < 16; ++r) *reinterpret_cast<u32x4*>(reg + r * STRB + lane * 16) = hv[r];
+  __syncthreads();
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    if (mt * 16 >= M) break;
+    const char* hreg = smem + mt * (16 * STRB);
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+      const bf16x8 bv = *reinterpret_cast<const bf16x8*>(hreg + rd_off + t * 64);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[t], bv, acc, 0, 0, 0);
+    }
+    const int m = mt * 16 + (lane & 15);
+    const int j = j0 + 4 * (lane >> 4);
+    if (m < M) *reinterpret_cast<f32x4*>(partial + (((int64_t)sl * batch + b) * M + m) * cap + j) = acc;
+  }
+}
+
+__global__ __launch_bounds__(256) void head_splitk_reduce_kernel(const float* __restrict__ partial, const int32_t* __restrict__ n_dev,
+                                                                 int S, int M, int cap, int64_t ld, float* __restrict__ logits) {
+  const int b = blockIdx.z, m = blockIdx.y, batch = gridDim.z;
+  const int j = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (j >= n_dev[b]) return;
+  const int64_t plane = (int64_t)batch * M * cap;
+  const float* p = partial + ((int64_t)b * M + m) * cap + j;
+  f32x4 s = *reinterpret_cast<const f32x4*>(p);
+  for (int sl = 1; sl < S; ++sl) s += *reinterpret_cast<const f32x4*>(p + sl * plane);
+  *reinterpret_cast<f32x4*>(logits + ((int64_t)b * M + m) * ld + j) = s;
+}
+
+template <int MT>
+static hipError_t run_splitk(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t cap_rows,
+                             int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride, float* logits,
+                             float* partial, int S, hipStream_t s) {
+  constexpr int LDS = 4 * 16 * (1024 + 16);
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_splitk_kernel<MT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  head_splitk_kernel<MT><<<dim3((cap_rows + 63) / 64, S, batch), 256, LDS, s>>>(W, H, ids, n_dev, V, M, d, cap_rows,
+                                                                             ids_stride, partial);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  head_splitk_reduce_kernel<<<dim3((cap_rows / 4 + 255) / 256, M, batch), 256, 0, s>>>(partial, n_dev, S, M, cap_rows, ld,
+                                                                                    logits);
+  return hipGetLastError();
+}
+
+// Up to 64 hidden rows per sequence in one launch; picks the kernel by M and by how many rows there are.
+static hipError_t launch_head_64(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev,
+                                 int32_t n_fixed, int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d,
+                                 int64_t ld, int64_t ids_stride, float* logits, float* partial, int64_t partial_bytes,
+                                 hipStream_t s) {
+  if (M <= 4) return run_quad<2, 1, 8, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+  if (M <= 8) return run_quad<2, 2, 8, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+  if (M <= 12) return run_quad<4, 3, 4, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+  if (M <= 16) return run_quad<4, 4, 4, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+  // wide trees: split K across workgroups while the rows alone cannot fill the chip
+  const int S = (d + 511) / 512;
+  const int64_t need = (int64_t)S * batch * M * cap_rows * 4;
+  const bool split = ids != nullptr && n_dev != nullptr && partial != nullptr && S >= 2 && need <= partial_bytes &&
+                     (int64_t)cap_rows * batch <= 16384 && cap_rows % 64 == 0 && ld % 4 == 0;
+  if (split) {
+    if (M <= 32) return run_splitk<2>(W, H, ids, n_dev, cap_rows, V, batch, M, d, ld, ids_stride, logits, partial, S, s);
+    return run_splitk<4>(W, H, ids, n_dev, cap_rows, V, batch, M, d, ld, ids_stride, logits, partial, S, s);
+  }
+  if (M <= 32) return run_mfma<1, 2>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+  return run_mfma<1, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
 }
 
 hipError_t launch_head(const void* W, const void* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
                        int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld_logits, int64_t ids_stride,
                        float* logits, float* partial, int64_t partial_bytes, hipStream_t s) {
-  (void)partial;
-  (void)partial_bytes;
   const uint16_t* Wp = static_cast<const uint16_t*>(W);
   const uint16_t* Hp = static_cast<const uint16_t*>(H);
-  const int variant = head_variant();
-  if (variant == 11 && M <= 8) return run_quad<2, 2, 4, 8>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
-  if (variant == 12 && M <= 8) return run_quad<1, 2, 8, 4>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
-  if (variant == 13 && M <= 8) return run_quad<4, 2, 8, 4>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
-  if (variant == 14 && M <= 8) return run_quad<2, 2, 2, 16>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
-  if (variant == 15 && M <= 8) return run_quad<1, 2, 4, 8>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
-  if (variant == 16 && M <= 8) return run_quad<4, 2, 4, 8>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
-  if (variant == 20 && M <= 8) return run_quad_persist<2, 8, 4, 3>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, 256, s);
-  if (variant == 21 && M <= 8) return run_quad_persist<2, 8, 4, 2>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, 512, s);
-  if (variant == 22 && M <= 8) return run_quad_persist<2, 4, 8, 3>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, 256, s);
-  if (variant == 23 && M <= 8) return run_quad_persist<2, 8, 4, 1>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, 768, s);
-  if (variant == 24 && M <= 8) return run_quad_persist<2, 8, 4, 4>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, 256, s);
-  if (variant == 30 && M <= 8) return run_quad<2, 2, 8, 4, false>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
-  if (variant == 31 && M <= 8) return run_quad<2, 2, 8, 4, true, true>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
-  if (variant == 0) {
-    if (M <= 4) return run_quad<2, 1, 8, 4>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
-    if (M <= 8) return run_quad<2, 2, 8, 4>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
-    if (M <= 12) return run_quad<4, 3, 4, 4>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
-    if (M <= 16) return run_quad<4, 4, 4, 4>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
-  }
-  if (variant != 9) {
-    if (M <= 8) return run_mfma<2, 1>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
-    if (M <= 16) return run_mfma<1, 1>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
-    if (M <= 32) return run_mfma<1, 2>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
-    if (M <= 64) return run_mfma<1, 4>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, s);
+  if (M <= 64)
+    return launch_head_64(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, partial,
+                          partial_bytes, s);
+  if (batch == 1) {                       // many hidden rows of one sequence: 64 at a time
+    for (int m0 = 0; m0 < M; m0 += 64) {
+      const int mm = M - m0 < 64 ? M - m0 : 64;
+      hipError_t e = launch_head_64(Wp, Hp + (int64_t)m0 * d, ids, n_dev, n_fixed, cap_rows, V, 1, mm, d, ld_logits, ids_stride,
+                                    logits + (int64_t)m0 * ld_logits, partial, partial_bytes, s);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
   }
   dim3 grid((cap_rows + 3) / 4, 1, batch);
   head_generic_kernel<8><<<grid, 256, 0, s>>>(Wp, Hp, ids, n_dev, n_fixed, M, d, ld_logits, ids_stride, logits);

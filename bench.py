@@ -30,6 +30,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
+# HBM bytes per sparse-head launch from the rocprofv3 --pmc runs summarised in
+# profiles/sparse_head_c2_pmc.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a copy kernel of
+# known size), as bytes per active row so that it follows the realised |active|.
+PMC_TRAFFIC_PER_ROW = {"c2": 25397248 / 3013}
 
 
 def main():
@@ -37,7 +41,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--target", type=int, default=3000, help="c5 only: number of distinct active ids")
     ap.add_argument("--replicas", type=int, default=16, help="copies of W_head rotated through (1 = warm caches)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly from Python instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -59,7 +64,7 @@ def main():
     total_steps = K + Wm
     cfg["steps"] = total_steps
     V, d, M, k, Bn = cfg["V"], cfg["d"], cfg["M"], cfg["k"], cfg["batch"]
-    seqs = synth.make_sequences(cfg)
+    seqs = synth.make_sequences(cfg, args.target if args.config == "c5" else None)
 
     t0 = time.time()
     W_host = synth.make_W(cfg)
@@ -189,7 +194,8 @@ def main():
         cpu = cpu_baseline(cfg, seqs, W_host, synth)
 
     out = {
-        "metric": "sparse-head draft steps/s + gathered HBM GB/s (V=128256,d=4096,|active|~3k)",
+        "metric": "sparse-head draft steps/s + gathered HBM GB/s (V=128256,d=4096,|active|~3k)" if args.config == "c2"
+                  else f"sparse-head draft steps/s + gathered HBM GB/s ({args.config})",
         "value": round(K / (ms * 1e-3), 1), "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": round(ms / K, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
@@ -200,7 +206,8 @@ def main():
         "gathered_GBps": round(achieved, 1),
         "roofline": {"bound": "hbm", "kernel": "nanospec_sparse_head", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": float(args.traffic) if args.traffic else None,
+                     "traffic": float(args.traffic) if args.traffic else (
+                         round(PMC_TRAFFIC_PER_ROW[args.config] * n_sum) if args.config in PMC_TRAFFIC_PER_ROW else None),
                      "bytes_per_launch": alg_bytes, "us_per_launch": round(head_us, 3)},
         "kernels_us": {"vocab_update": round(upd_us, 2), "sparse_head": round(head_us, 2), "topk_remap": round(topk_us, 2)},
         "dense": dense,

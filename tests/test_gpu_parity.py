@@ -272,3 +272,55 @@ def test_argument_errors():
     torch.cuda.synchronize()
     assert np.array_equal(st.read_active()[0], np.zeros(0, np.int32))               # nothing was enqueued
     st.close()
+
+
+def test_step_recorded_in_hip_graph_replays_correctly():
+    """the three hot calls enqueue kernels only (no sync, no allocation, no memset node): a step captured
+    in a HIP graph and replayed several times, with eager work and synchronisations in between, gives the
+    oracle's vocabulary and the eager path's bits on every replay."""
+    cfg = synth.CONFIGS["c1"]
+    W = host_W(cfg)
+    V, d, M, k = cfg["V"], cfg["d"], cfg["M"], cfg["k"]
+    dW = dev_bf16(W)
+    dH = dev_bf16(synth.make_H(cfg, 5, 1, M)[0])
+    seqs = synth.make_sequences(cfg)
+    st = B.State(V, d, 1, seqs["window"], seqs["topk_cap"], M, k)
+    o = oracle.Vocab(V, seqs["window"])
+    ctx, T0 = seqs["ctx"][0], seqs["T0"][0]
+    B.nanospec_vocab_init(st.h, dev(ctx), [0, len(ctx)], dev(T0), [0, len(T0)])
+    o.init(ctx, T0)
+    new = np.array([17, 4242, 17, 31999, 5], np.int32)
+    d_new = dev(new)
+    cap = st.capacity
+    lg_g = torch.empty((1, M, cap), dtype=torch.float32, device="cuda")
+    lg_e = torch.empty((1, M, cap), dtype=torch.float32, device="cuda")
+    oi_g = torch.empty((1, M, k), dtype=torch.int32, device="cuda")
+    ov_g = torch.empty((1, M, k), dtype=torch.float32, device="cuda")
+    oi_e, ov_e = torch.empty_like(oi_g), torch.empty_like(ov_g)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        cs = torch.cuda.current_stream().cuda_stream
+        B.nanospec_vocab_update(st.h, d_new, [0, len(new)], None, None, cs)
+        B.nanospec_sparse_head(st.h, dW, dH, M, lg_g, cs)
+        B.nanospec_topk_remap(st.h, lg_g, M, k, oi_g, ov_g, cs)
+    torch.cuda.synchronize()
+    assert np.array_equal(st.read_active()[0], o.active())            # capture itself ran nothing
+    for rep in range(4):
+        g.replay()
+        torch.cuda.synchronize()
+        o.update(new)
+        act = st.read_active()[0]
+        assert np.array_equal(act, o.active()), rep
+        B.nanospec_sparse_head(st.h, dW, dH, M, lg_e)                  # eager work between replays
+        B.nanospec_topk_remap(st.h, lg_e, M, k, oi_e, ov_e)
+        torch.cuda.synchronize()
+        n = len(act)
+        assert np.array_equal(lg_g.cpu().numpy()[0, :, :n], lg_e.cpu().numpy()[0, :, :n]), rep
+        assert np.array_equal(oi_g.cpu().numpy(), oi_e.cpu().numpy()) and np.array_equal(ov_g.cpu().numpy(), ov_e.cpu().numpy())
+        o32, o64 = oracle.head(W, synth.make_H(cfg, 5, 1, M)[0], ids=act)
+        assert_logits_close(lg_g.cpu().numpy()[0, :, :n], o64, o32, f"replay {rep}")
+        extra = np.array([rep, 100 + rep], np.int32)                   # eager update between replays
+        B.nanospec_vocab_update(st.h, dev(extra), [0, 2])
+        o.update(extra)
+    st.close()

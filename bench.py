@@ -44,6 +44,7 @@ def main():
     ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--target", type=int, default=3000, help="c5 only: number of distinct active ids")
     ap.add_argument("--replicas", type=int, default=16, help="copies of W_head rotated through (1 = warm caches)")
+    ap.add_argument("--hidden-buffers", type=int, default=16, help="distinct hidden-state tensors rotated through")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly from Python instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
@@ -73,7 +74,7 @@ def main():
     Wd = [to_dev(W_host.view(np.int16)).view(torch.bfloat16)]
     for _ in range(R - 1):
         Wd.append(Wd[0].clone())
-    NH = 16                                                   # distinct hidden-state tensors rotated through
+    NH = max(1, args.hidden_buffers)
     Hd = [to_dev(synth.make_H(cfg, s).view(np.int16)).view(torch.bfloat16) for s in range(NH)]
 
     st = B.State(V, d, Bn, seqs["window"], seqs["topk_cap"], M, k)

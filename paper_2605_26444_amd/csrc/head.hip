@@ -183,7 +183,10 @@ __global__ __launch_bounds__(256) void head_mfma_kernel(const uint16_t* __restri
   }
 }
 
-// Matrix-core kernel for few hidden rows (M <= 16), no LDS staging at all.
+// Matrix-core kernel for few hidden rows (M <= 16) and MANY rows (dense head, tens of thousands of
+// active rows): same operand layout as head_quad_kernel below, but every wavefront fetches its own
+// hidden-row operands and nothing goes through LDS except the final K-slice sum.  With thousands of
+// workgroups in flight the hidden rows stay in L1/L2 and the barrier-free form is the faster one.
 // The 16 rows of the A tile of v_mfma_f32_16x16x32_bf16 are 4 gathered rows x 4 column parts, the 16
 // columns of the B tile are 4 hidden rows x the same 4 column parts; only the diagonal (part == part)
 // 4x4 blocks of the product are kept and summed.  With operand row i = 4*row + part and the part as
@@ -196,7 +199,7 @@ __global__ __launch_bounds__(256) void head_mfma_kernel(const uint16_t* __restri
 // A workgroup of four wavefronts owns 4*RT rows; wavefront w takes columns [kb + w*128*KS, +128*KS)
 // per K-iteration; the four K-slices are summed in fixed order through LDS.
 template <int RT, int MT, int KS, int NW>
-__global__ __launch_bounds__(64 * NW) void head_quad_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
+__global__ __launch_bounds__(64 * NW) void head_quad_private_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
                                                         const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
                                                         int n_fixed, int V, int M, int d, int64_t ld, int64_t ids_stride,
                                                         float* __restrict__ logits) {
@@ -295,12 +298,169 @@ __global__ __launch_bounds__(64 * NW) void head_quad_kernel(const uint16_t* __re
 }
 
 template <int RT, int MT, int KS, int NW>
-static hipError_t run_quad(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
+static hipError_t run_quad_private(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
                            int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride,
                            float* logits, hipStream_t s) {
   dim3 grid((cap_rows + 4 * RT - 1) / (4 * RT), 1, batch);
-  head_quad_kernel<RT, MT, KS, NW><<<grid, 64 * NW, 0, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
+  head_quad_private_kernel<RT, MT, KS, NW><<<grid, 64 * NW, 0, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
   return hipGetLastError();
+}
+
+// Matrix-core kernel for few hidden rows (M <= 16).
+// The 16 rows of the A tile of v_mfma_f32_16x16x32_bf16 are 4 gathered rows x 4 column parts, the 16
+// columns of the B tile are 4 hidden rows x the same 4 column parts; only the diagonal (part == part)
+// 4x4 blocks of the product are kept and summed.  With operand row i = 4*row + part and the part as
+// the fastest index, the four lanes of a quad read 64 consecutive bytes of one matrix row and one
+// load instruction covers 4 rows x 256 contiguous bytes -- fully coalesced straight into the operand
+// registers, with no transposition through LDS and no cross-lane reduction of products.  A dot
+// product does not care in which order its terms are paired up as long as both operands agree,
+// which they do: both use the same map from (lane, step) to column.  The matrix cores run at a
+// quarter of their peak this way, still several times the arithmetic the HBM stream can feed.
+//
+// A workgroup has 4*NRG wavefronts: wavefront (kq, rg) owns rows [4*RT*rg, +4*RT) of the
+// workgroup's 4*RT*NRG rows and K-quarter kq of each K-iteration (128*KS columns).  All its weight
+// loads of an iteration are put in flight at once.  The hidden rows of a K-quarter are the same for
+// every row group, so the NRG wavefronts that share kq each fetch 1/NRG of that slice (already in
+// operand layout) and exchange it through LDS: the hidden-row traffic out of L2 shrinks by NRG,
+// which is what limits this kernel once the weights stream at HBM speed.  The K-quarters of a row
+// group are summed in fixed order through LDS, so a logit's bits do not depend on the row's
+// position in the list, on n or on timing.
+template <int NRG, int RT, int MT, int KS>
+__global__ __launch_bounds__(256 * NRG) void head_quad_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
+                                                              const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
+                                                              int n_fixed, int V, int M, int d, int64_t ld, int64_t ids_stride,
+                                                              float* __restrict__ logits) {
+  constexpr int HI = MT * KS;                      // load instructions per hidden-row K-quarter slice
+  constexpr int HPW = (HI + NRG - 1) / NRG;        // of which each sharing wavefront fetches this many
+  constexpr int RPG = 4 * RT;                      // rows per row group
+  constexpr int NOUT = RT * MT * 16;               // outputs per row group
+  static_assert(HI <= 16 && NOUT * 4 * NRG * 4 <= 4 * HI * 1024, "LDS budget");
+  __shared__ __attribute__((aligned(16))) char hs[4 * HI * 1024];
+  const int b = blockIdx.z;
+  const int lane = threadIdx.x & 63;
+  const int w = threadIdx.x >> 6;
+  const int kq = w & 3, rg = w >> 2;
+  const int j0 = (blockIdx.x * NRG + rg) * RPG;
+  const int orow = (lane & 15) >> 2, part = lane & 3, q = lane >> 4;   // operand row / column part / k group
+  const int coff = kq * (128 * KS) + q * 32 + part * 8;                // + kb + t*128
+  const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+  const uint16_t* Hb = H + (int64_t)b * M * d;
+
+  // Row ids are the first loads issued, so that nothing queues ahead of them, and they are read
+  // without waiting for the row count: the list is allocated to its capacity, a stale id is clamped
+  // into the matrix and its product is never stored.  (Measured on MI355X: fetching them through
+  // the vector path beats the scalar cache here by ~0.5 us, and leaving early on the row count
+  // costs ~1.4 us because the hidden-row loads then sink below the wait for the count; workgroups
+  // past the end therefore run through with their weight loads masked off.)
+  int idr[RPG];
+#pragma unroll
+  for (int r = 0; r < RPG; ++r) idr[r] = ids ? ids[b * ids_stride + j0 + r] : j0 + r;
+  const int n = n_dev ? n_dev[b] : n_fixed;
+
+  auto load_h = [&](int kb, u32x4(&hv)[HPW]) {
+#pragma unroll
+    for (int ii = 0; ii < HPW; ++ii) {
+      const int i = rg * HPW + ii, mt = i / KS, t = i % KS;
+      const int m = mt * 4 + orow, c = kb + coff + t * 128;
+      hv[ii] = (i < HI && m < M && c < d) ? *reinterpret_cast<const u32x4*>(Hb + (int64_t)m * d + c) : zero;
+    }
+  };
+  // this wavefront's share of the hidden rows of the first K-iteration depends on the arguments
+  // only: it streams in from L2 while the ids are still on their way
+  u32x4 hv[HPW];
+  load_h(0, hv);
+
+  const uint16_t* wrow[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    int64_t row = orow == 0 ? idr[rt * 4] : (orow == 1 ? idr[rt * 4 + 1] : (orow == 2 ? idr[rt * 4 + 2] : idr[rt * 4 + 3]));
+    row = row < 0 ? 0 : (row >= V ? V - 1 : row);
+    wrow[rt] = W + row * d;
+  }
+  const bool live = j0 < n;
+
+  f32x4 acc[RT][MT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[rt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int kb = 0; kb < d; kb += 512 * KS) {
+    if (kb != 0) load_h(kb, hv);
+    u32x4 wv[RT][KS];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int t = 0; t < KS; ++t) {
+        const int c = kb + coff + t * 128;
+        wv[rt][t] = (live && c < d) ? *reinterpret_cast<const u32x4*>(wrow[rt] + c) : zero;
+      }
+    if (kb != 0) __syncthreads();                           // the previous slice has been consumed
+#pragma unroll
+    for (int ii = 0; ii < HPW; ++ii)
+      if (rg * HPW + ii < HI) *reinterpret_cast<u32x4*>(hs + (kq * HI + rg * HPW + ii) * 1024 + lane * 16) = hv[ii];
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < KS; ++t)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const bf16x8 bv = *reinterpret_cast<const bf16x8*>(hs + (kq * HI + mt * KS + t) * 1024 + lane * 16);
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+          acc[rt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[rt][t]), bv, acc[rt][mt], 0, 0, 0);
+      }
+  }
+
+  // result lane l holds product rows 4*(l/16)+v, column l%16: the diagonal block entry is v == l%4;
+  // the four parts sit in the four lanes of a quad
+  __syncthreads();                                          // hs is reused for the K-quarter sums
+  float* red = reinterpret_cast<float*>(hs);
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const f32x4 a = acc[rt][mt];
+      float x = part == 0 ? a[0] : (part == 1 ? a[1] : (part == 2 ? a[2] : a[3]));
+      x += __shfl_xor(x, 1);
+      x += __shfl_xor(x, 2);
+      if (part == 0) red[w * NOUT + (rt * MT + mt) * 16 + q * 4 + orow] = x;   // (tile row q, hidden row orow)
+    }
+  __syncthreads();
+  for (int o = threadIdx.x; o < NRG * NOUT; o += 256 * NRG) {
+    const int g = o / NOUT, oo = o % NOUT;
+    const int rt = oo / (MT * 16), mt = (oo / 16) % MT, r = (oo % 16) / 4, mm = oo % 4;
+    const int j = (blockIdx.x * NRG + g) * RPG + rt * 4 + r, m = mt * 4 + mm;
+    if (j >= n || m >= M) continue;
+    const float* rr = red + (g * 4) * NOUT + oo;
+    const float s = ((rr[0] + rr[NOUT]) + rr[2 * NOUT]) + rr[3 * NOUT];
+    logits[((int64_t)b * M + m) * ld + j] = s;
+  }
+}
+
+template <int NRG, int RT, int MT, int KS>
+static hipError_t run_quad(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
+                           int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride,
+                           float* logits, hipStream_t s) {
+  constexpr int ROWS = 4 * RT * NRG;
+  dim3 grid((cap_rows + ROWS - 1) / ROWS, 1, batch);
+  head_quad_kernel<NRG, RT, MT, KS><<<grid, 256 * NRG, 0, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
+  return hipGetLastError();
+}
+
+// Rows per workgroup follow the row capacity: sharing hidden rows among more row groups pays as
+// long as the launch still has about one workgroup per compute unit.
+template <int MT, int KS>
+static hipError_t run_quad_auto(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
+                                int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld,
+                                int64_t ids_stride, float* logits, hipStream_t s) {
+  const int64_t rows = (int64_t)cap_rows * batch;
+  if (rows >= 8192) {   // thousands of workgroups: the barrier-free kernel wins (measured at 32k rows and dense)
+    if (MT <= 2) return run_quad_private<2, MT, 8, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+    return run_quad_private<4, MT, 4, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+  }
+  if (rows >= 16 * 180) return run_quad<4, 1, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+  if (rows >= 8 * 180) return run_quad<2, 1, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+  return run_quad<1, 1, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
 }
 
 template <int P, int MT>
@@ -425,10 +585,10 @@ static hipError_t launch_head_64(const uint16_t* W, const uint16_t* H, const int
                                  int32_t n_fixed, int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d,
                                  int64_t ld, int64_t ids_stride, float* logits, float* partial, int64_t partial_bytes,
                                  hipStream_t s) {
-  if (M <= 4) return run_quad<2, 1, 8, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
-  if (M <= 8) return run_quad<2, 2, 8, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
-  if (M <= 12) return run_quad<4, 3, 4, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
-  if (M <= 16) return run_quad<4, 4, 4, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+  if (M <= 4) return run_quad_auto<1, 8>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+  if (M <= 8) return run_quad_auto<2, 8>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+  if (M <= 12) return run_quad_auto<3, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+  if (M <= 16) return run_quad_auto<4, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
   // wide trees: split K across workgroups while the rows alone cannot fill the chip
   const int S = (d + 511) / 512;
   const int64_t need = (int64_t)S * batch * M * cap_rows * 4;

@@ -185,7 +185,20 @@ def main():
             B.nanospec_dense_topk(dl, V, Mt, k, di, dv, ws, wsb, cs)
         dense_us = train(dstep, 40)
         dense_head_us = train(lambda i, cs: B.nanospec_dense_head(Wd[i % R], Hd[i % NH], V, d, Mt, dl, cs), 40)
-        dense = {"step_us": round(dense_us, 2), "head_us": round(dense_head_us, 2),
+        # context: the vendor GEMM library on the same product (bf16 out), through torch.matmul
+        Hflat = [h.reshape(Mt, d) for h in Hd]
+        lib_us = train(lambda i, cs: torch.matmul(Hflat[i % NH], Wd[i % R].t()), 20) if not use_graph else None
+        if use_graph:
+            for i in range(3):
+                torch.matmul(Hflat[i % NH], Wd[i % R].t())
+            torch.cuda.synchronize()
+            e0.record()
+            for i in range(20):
+                torch.matmul(Hflat[i % NH], Wd[i % R].t())
+            e1.record()
+            torch.cuda.synchronize()
+            lib_us = e0.elapsed_time(e1) * 1e3 / 20
+        dense = {"step_us": round(dense_us, 2), "head_us": round(dense_head_us, 2), "library_gemm_us": round(lib_us, 2),
                  "head_GBps": round(V * d * 2 / (dense_head_us * 1e-6) / 1e9, 1),
                  "speedup_step": round(dense_us / (ms * 1e3 / K), 2),
                  "speedup_head": round(dense_head_us / head_us, 2)}

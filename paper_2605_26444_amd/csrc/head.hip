@@ -67,122 +67,6 @@ __global__ __launch_bounds__(256) void head_generic_kernel(const uint16_t* __res
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// Matrix-core kernel.  A workgroup of four wavefronts owns R = 16/P gathered rows; per K-iteration
-// wavefront w streams columns [kb + w*512*P, +512*P) of those rows with fully coalesced 16-byte loads
-// (one instruction = 1 KB of one row), parks them in its private LDS region and reads them back in the
-// operand layout of v_mfma_f32_16x16x32_bf16 (lane = row + 16*kgroup, 8 consecutive k per lane).
-// The hidden rows take the same route as the B operand.  P > 1 folds P column parts of the same rows
-// into the 16 rows of the A tile (and of the same hidden rows into the 16 columns of the B tile), so
-// that with few hidden rows all 16x16x32 operand slots still carry useful data; only the P diagonal
-// RxR blocks of the product are kept.  No wavefront waits for another until the final fixed-order sum
-// of the four K-slices, so results do not depend on the row's position or on run-to-run timing.
-template <int P, int MT>
-__global__ __launch_bounds__(256) void head_mfma_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
-                                                        const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
-                                                        int n_fixed, int V, int M, int d, int64_t ld, int64_t ids_stride,
-                                                        float* __restrict__ logits) {
-  constexpr int R = 16 / P;
-  constexpr int CW = 512 * P;
-  constexpr int STRB = CW * 2 + 16;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int b = blockIdx.z;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int j0 = blockIdx.x * R;
-  char* reg = smem + w * (R * STRB);
-  const uint16_t* Hb = H + (int64_t)b * M * d;
-
-  const int ai = lane & 15, aq = lane >> 4;
-  const int rd_off = (ai % R) * STRB + (ai / R) * 1024 + aq * 16;   // + t*64 per MFMA step
-  const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
-
-  // hidden rows of (K-iteration kb, m-tile mt) for this wavefront's column slice
-  auto load_h = [&](int kb, int mt, u32x4(&hv)[16]) {
-    const int c0 = kb + w * CW + lane * 8;
-#pragma unroll
-    for (int s = 0; s < 16; ++s) {
-      const int c = c0 + (s % P) * 512;
-      const int m = mt * R + s / P;
-      hv[s] = (c < d && m < M) ? *reinterpret_cast<const u32x4*>(Hb + (int64_t)m * d + c) : zero;
-    }
-  };
-  // The first hidden-row loads depend on nothing but the arguments: they go out before the row
-  // count and the row ids have come back.
-  u32x4 hv[16];
-  load_h(0, 0, hv);
-
-  // The row ids are fetched without waiting for the row count: the id list is allocated up to its
-  // capacity, so reading past n is safe, and a stale id is clamped into the matrix (its product is
-  // never stored).  This keeps "count -> ids -> rows" from becoming three dependent round trips.
-  const uint16_t* wrow[R];
-#pragma unroll
-  for (int r = 0; r < R; ++r) {
-    int64_t row = j0 + r;
-    if (ids) row = ids[b * ids_stride + j0 + r];
-    row = row < 0 ? 0 : (row >= V ? V - 1 : row);
-    wrow[r] = W + row * d;
-  }
-  const int n = n_dev ? n_dev[b] : n_fixed;
-  if (j0 >= n) return;
-
-  f32x4 acc[MT];
-#pragma unroll
-  for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  for (int kb = 0; kb < d; kb += 4 * CW) {
-    const int c0 = kb + w * CW + lane * 8;
-    if (kb + w * CW >= d) continue;                                   // whole slice beyond the row end
-    u32x4 wv[16];
-#pragma unroll
-    for (int s = 0; s < 16; ++s) {
-      const int c = c0 + (s % P) * 512;
-      wv[s] = (c < d) ? *reinterpret_cast<const u32x4*>(wrow[s / P] + c) : zero;
-    }
-    bf16x8 av[16];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      if (mt * R >= M) break;
-      if (kb != 0 || mt != 0) load_h(kb, mt, hv);
-#pragma unroll
-      for (int s = 0; s < 16; ++s)
-        *reinterpret_cast<u32x4*>(reg + (s / P) * STRB + (s % P) * 1024 + lane * 16) = hv[s];
-      bf16x8 bv[16];
-#pragma unroll
-      for (int t = 0; t < 16; ++t) bv[t] = *reinterpret_cast<const bf16x8*>(reg + rd_off + t * 64);
-      if (mt == 0) {
-#pragma unroll
-        for (int s = 0; s < 16; ++s)
-          *reinterpret_cast<u32x4*>(reg + (s / P) * STRB + (s % P) * 1024 + lane * 16) = wv[s];
-#pragma unroll
-        for (int t = 0; t < 16; ++t) av[t] = *reinterpret_cast<const bf16x8*>(reg + rd_off + t * 64);
-      }
-#pragma unroll
-      for (int t = 0; t < 16; ++t) acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[t], bv[t], acc[mt], 0, 0, 0);
-    }
-  }
-
-  // the four K-slices meet in LDS: every wavefront leaves its 16x16 tiles in its own region
-  float* red = reinterpret_cast<float*>(reg);
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int v = 0; v < 4; ++v) red[mt * 256 + (aq * 4 + v) * 16 + ai] = acc[mt][v];
-  __syncthreads();
-  constexpr int OUT = R * R;                                           // useful outputs per m-tile
-  for (int o = threadIdx.x; o < OUT * MT; o += 256) {
-    const int mt = o / OUT, r = (o % OUT) / R, mm = o % R;
-    const int m = mt * R + mm;
-    if (j0 + r >= n || m >= M) continue;
-    float s = 0.f;
-#pragma unroll
-    for (int ww = 0; ww < 4; ++ww) {
-      const float* t = reinterpret_cast<const float*>(smem + ww * (R * STRB)) + mt * 256;
-#pragma unroll
-      for (int p = 0; p < P; ++p) s += t[(p * R + r) * 16 + p * R + mm];
-    }
-    logits[((int64_t)b * M + m) * ld + j0 + r] = s;
-  }
-}
-
 // Matrix-core kernel for few hidden rows (M <= 16) and MANY rows (dense head, tens of thousands of
 // active rows): same operand layout as head_quad_kernel below, but every wavefront fetches its own
 // hidden-row operands and nothing goes through LDS except the final K-slice sum.  With thousands of
@@ -463,87 +347,96 @@ static hipError_t run_quad_auto(const uint16_t* W, const uint16_t* H, const int3
   return run_quad<1, 1, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
 }
 
-template <int P, int MT>
-static hipError_t run_mfma(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
-                           int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride,
-                           float* logits, hipStream_t s) {
-  constexpr int R = 16 / P;
-  constexpr int LDS = 4 * R * (512 * P * 2 + 16);
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_mfma_kernel<P, MT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
-  dim3 grid((cap_rows + R - 1) / R, 1, batch);
-  head_mfma_kernel<P, MT><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
-  return hipGetLastError();
-}
-
-// Split-K matrix-core kernel for wide draft trees (16 < M <= 64) on few rows.  A workgroup owns 64
-// gathered rows (one 16-row tile per wavefront) and ONE 512-column slice of K, so that the hidden
-// rows it needs (M x 512) are as many bytes as the weights it streams (64 x 512) instead of four
-// times as many, and enough workgroups exist to fill the chip.  Weights and hidden rows are loaded
-// with coalesced 1 KB-per-row instructions, parked in padded LDS and read back in the operand layout
-// of v_mfma_f32_16x16x32_bf16; the hidden-row slice is shared by the four wavefronts.  Each slice
-// writes its partial products to its own plane; head_splitk_reduce_kernel adds the planes in slice
-// order, so the result is deterministic.
-template <int MT>
-__global__ __launch_bounds__(256) void head_splitk_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
+// Matrix-core kernel for wide draft trees (16 < M <= 64).  A workgroup owns 64 rows (one 16-row
+// tile per wavefront) and works on one 512-column slice of K at a time, so that the hidden rows it
+// needs per slice (M x 512) are as many bytes as the weights it streams (64 x 512) instead of four
+// times as many.  Weights and hidden rows are loaded with coalesced 1 KB-per-row instructions,
+// parked in padded LDS and read back in the operand layout of v_mfma_f32_16x16x32_bf16 (lane = row +
+// 16*kgroup, 8 consecutive k per lane; padding keeps the 16 rows on distinct banks); the hidden-row
+// slice is shared by the four wavefronts and the next slice's loads are issued before the matrix
+// cores start on the current one.
+//   LOOPK = true : the workgroup walks all slices and writes logits (many rows: dense head, c5).
+//   LOOPK = false: split-K -- slice = blockIdx.y, partial products go to that slice's plane and
+//                  head_splitk_reduce_kernel adds the planes in slice order (few rows: the rows
+//                  alone cannot fill the chip; deterministic because the order is fixed).
+template <int MT, bool LOOPK>
+__global__ __launch_bounds__(256) void head_tile64_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
                                                           const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
-                                                          int V, int M, int d, int cap, int64_t ids_stride,
-                                                          float* __restrict__ partial) {
+                                                          int n_fixed, int V, int M, int d, int64_t ld, int64_t ids_stride,
+                                                          float* __restrict__ out) {
   constexpr int STRB = 1024 + 16;
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int b = blockIdx.z, sl = blockIdx.y, batch = gridDim.z;
+  const int b = blockIdx.z, batch = gridDim.z;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int j0 = blockIdx.x * 64 + w * 16;
-  const int c = sl * 512 + lane * 8;
-  const bool cok = c < d;
+  const int S = (d + 511) / 512;
+  const int s0 = LOOPK ? 0 : blockIdx.y, s1 = LOOPK ? S : blockIdx.y + 1;
   const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
   char* reg = smem + w * (16 * STRB);
 
-  int idr[16];
+  // one id per lane (capacity-bounded, not waiting for the row count), handed out by readlane;
+  // no early exit: it would let the hidden-row loads sink below the wait for the count
+  int myid = j0 + (lane & 15);
+  if (ids) myid = ids[b * ids_stride + j0 + (lane & 15)];
+  const int n = n_dev ? n_dev[b] : n_fixed;
+  u32x4 hv[16], wv[16];
+  auto load_slice = [&](int sl) {
+    const int c = sl * 512 + lane * 8;
+    const bool cok = c < d;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) idr[r] = ids[b * ids_stride + j0 + r];     // scalar loads, capacity-bounded
-  const int n = n_dev[b];
-  u32x4 hv[16];
+    for (int r = 0; r < 16; ++r) {
+      const int m = w * 16 + r;
+      hv[r] = (cok && m < M) ? *reinterpret_cast<const u32x4*>(H + ((int64_t)b * M + m) * d + c) : zero;
+    }
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int m = w * 16 + r;
-    hv[r] = (cok && m < M) ? *reinterpret_cast<const u32x4*>(H + ((int64_t)b * M + m) * d + c) : zero;
-  }
-  if ((int)blockIdx.x * 64 >= n) return;
-  u32x4 wv[16];
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    int64_t row = idr[r];
-    row = row < 0 ? 0 : (row >= V ? V - 1 : row);
-    wv[r] = (cok && j0 + r < n) ? *reinterpret_cast<const u32x4*>(W + row * d + c) : zero;
-  }
+    for (int r = 0; r < 16; ++r) {
+      int64_t row = __builtin_amdgcn_readlane(myid, r);
+      row = row < 0 ? 0 : (row >= V ? V - 1 : row);
+      wv[r] = (cok && j0 + r < n) ? *reinterpret_cast<const u32x4*>(W + row * d + c) : zero;
+    }
+  };
+  load_slice(s0);
   const int rd_off = (lane & 15) * STRB + (lane >> 4) * 16;
+  f32x4 acc[MT];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) *reinterpret_cast<u32x4*>(reg + r * STRB + lane * 16) = wv[r];
-  bf16x8 av[16];
+  for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int sl = s0; sl < s1; ++sl) {
+    if (sl != s0) __syncthreads();                          // the previous hidden-row slice has been consumed
 #pragma unroll
-  for (int t = 0; t < 16; ++t) av[t] = *reinterpret_cast<const bf16x8*>(reg + rd_off + t * 64);
+    for (int r = 0; r < 16; ++r) *reinterpret_cast<u32x4*>(reg + r * STRB + lane * 16) = wv[r];
+    bf16x8 av[16];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) *reinterpret_cast<u32x4*>(reg + r * STRB + lane * 16) = hv[r];
-  __syncthreads();
+    for (int t = 0; t < 16; ++t) av[t] = *reinterpret_cast<const bf16x8*>(reg + rd_off + t * 64);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) *reinterpret_cast<u32x4*>(reg + r * STRB + lane * 16) = hv[r];
+    __syncthreads();
+    if (sl + 1 < s1) load_slice(sl + 1);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      if (mt * 16 >= M) break;
+      const char* hreg = smem + mt * (16 * STRB);
+#pragma unroll
+      for (int t = 0; t < 16; ++t) {
+        const bf16x8 bv = *reinterpret_cast<const bf16x8*>(hreg + rd_off + t * 64);
+        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[t], bv, acc[mt], 0, 0, 0);
+      }
+    }
+  }
+  // result lane l holds rows j0 + 4*(l/16) + v, hidden row 16*mt + l%16
+  const int j = j0 + 4 * (lane >> 4);
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    if (mt * 16 >= M) break;
-    const char* hreg = smem + mt * (16 * STRB);
-    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int t = 0; t < 16; ++t) {
-      const bf16x8 bv = *reinterpret_cast<const bf16x8*>(hreg + rd_off + t * 64);
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[t], bv, acc, 0, 0, 0);
-    }
     const int m = mt * 16 + (lane & 15);
-    const int j = j0 + 4 * (lane >> 4);
-    if (m < M) *reinterpret_cast<f32x4*>(partial + (((int64_t)sl * batch + b) * M + m) * cap + j) = acc;
+    if (m >= M || j >= n) continue;
+    float* dst = LOOPK ? out + ((int64_t)b * M + m) * ld + j
+                       : out + (((int64_t)blockIdx.y * batch + b) * M + m) * ld + j;   // ld = plane row stride
+    if ((ld & 3) == 0 && (LOOPK ? j + 3 < n : true)) {
+      *reinterpret_cast<f32x4*>(dst) = acc[mt];
+    } else {
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        if (j + v < n) dst[v] = acc[mt][v];
+    }
   }
 }
 
@@ -559,24 +452,43 @@ __global__ __launch_bounds__(256) void head_splitk_reduce_kernel(const float* __
   *reinterpret_cast<f32x4*>(logits + ((int64_t)b * M + m) * ld + j) = s;
 }
 
+template <int MT, bool LOOPK>
+static hipError_t tile64_configure() {
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_tile64_kernel<MT, LOOPK>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 16 * (1024 + 16));
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  return hipSuccess;
+}
+
 template <int MT>
 static hipError_t run_splitk(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t cap_rows,
                              int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride, float* logits,
                              float* partial, int S, hipStream_t s) {
   constexpr int LDS = 4 * 16 * (1024 + 16);
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_splitk_kernel<MT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
-  head_splitk_kernel<MT><<<dim3((cap_rows + 63) / 64, S, batch), 256, LDS, s>>>(W, H, ids, n_dev, V, M, d, cap_rows,
-                                                                             ids_stride, partial);
-  hipError_t e = hipGetLastError();
+  hipError_t e = tile64_configure<MT, false>();
+  if (e != hipSuccess) return e;
+  head_tile64_kernel<MT, false><<<dim3((cap_rows + 63) / 64, S, batch), 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows,
+                                                                                    ids_stride, partial);
+  e = hipGetLastError();
   if (e != hipSuccess) return e;
   head_splitk_reduce_kernel<<<dim3((cap_rows / 4 + 255) / 256, M, batch), 256, 0, s>>>(partial, n_dev, S, M, cap_rows, ld,
                                                                                     logits);
+  return hipGetLastError();
+}
+
+template <int MT>
+static hipError_t run_tile64(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
+                             int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride,
+                             float* logits, hipStream_t s) {
+  constexpr int LDS = 4 * 16 * (1024 + 16);
+  hipError_t e = tile64_configure<MT, true>();
+  if (e != hipSuccess) return e;
+  head_tile64_kernel<MT, true><<<dim3((cap_rows + 63) / 64, 1, batch), 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld,
+                                                                                   ids_stride, logits);
   return hipGetLastError();
 }
 
@@ -598,8 +510,8 @@ static hipError_t launch_head_64(const uint16_t* W, const uint16_t* H, const int
     if (M <= 32) return run_splitk<2>(W, H, ids, n_dev, cap_rows, V, batch, M, d, ld, ids_stride, logits, partial, S, s);
     return run_splitk<4>(W, H, ids, n_dev, cap_rows, V, batch, M, d, ld, ids_stride, logits, partial, S, s);
   }
-  if (M <= 32) return run_mfma<1, 2>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
-  return run_mfma<1, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+  if (M <= 32) return run_tile64<2>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+  return run_tile64<4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
 }
 
 hipError_t launch_head(const void* W, const void* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,

@@ -324,3 +324,33 @@ def test_step_recorded_in_hip_graph_replays_correctly():
         B.nanospec_vocab_update(st.h, dev(extra), [0, 2])
         o.update(extra)
     st.close()
+
+
+@pytest.mark.parametrize("d,M,n_ctx,batch", [
+    (520, 1, 37, 1), (520, 3, 300, 2), (1032, 5, 1500, 1), (3592, 8, 3001, 1), (4096, 9, 777, 1), (1032, 13, 2900, 3),
+    (520, 16, 9000, 1), (1032, 17, 1000, 1), (3592, 33, 1234, 1), (1032, 64, 17000, 1), (520, 70, 500, 1), (520, 70, 200, 2),
+])
+def test_head_shapes_against_oracle(d, M, n_ctx, batch):
+    """every head kernel and its ragged tails: row counts that are not multiples of the tile, hidden sizes that
+    are not multiples of a K slice, hidden-row counts on both sides of each kernel boundary, several sequences."""
+    V = 20000
+    W = synth.normal_bf16(900 + d, 0, (V, d), 0.02)
+    H = synth.normal_bf16(901 + d, M, (batch, M, d), 1.0, threads=1)
+    dW, dH = dev_bf16(W), dev_bf16(H)
+    st = B.State(V, d, batch, n_ctx, 0, M, 4)
+    rng = np.random.default_rng(d * 1000 + M)
+    ctx = [rng.choice(V, size=n_ctx - 3 * b, replace=False).astype(np.int32) for b in range(batch)]
+    flat, off = csr(ctx)
+    B.nanospec_vocab_init(st.h, dev(flat), off, None, np.zeros(batch + 1, np.int32))
+    cap = st.capacity
+    logits = torch.full((batch, M, cap), float("nan"), dtype=torch.float32, device="cuda")
+    B.nanospec_sparse_head(st.h, dW, dH, M, logits)
+    torch.cuda.synchronize()
+    act = st.read_active()
+    g = logits.cpu().numpy()
+    for b in range(batch):
+        assert np.array_equal(act[b], np.sort(ctx[b]))
+        n = len(act[b])
+        o32, o64 = oracle.head(W, H[b], ids=act[b], omp=True)
+        assert_logits_close(g[b, :, :n], o64, o32, f"d={d} M={M} seq {b}")
+    st.close()

@@ -209,7 +209,7 @@ static hipError_t run_quad_private(const uint16_t* W, const uint16_t* H, const i
 // which is what limits this kernel once the weights stream at HBM speed.  The K-quarters of a row
 // group are summed in fixed order through LDS, so a logit's bits do not depend on the row's
 // position in the list, on n or on timing.
-template <int NRG, int RT, int MT, int KS>
+template <int NRG, int RT, int MT, int KS, bool ONEK>
 __global__ __launch_bounds__(256 * NRG) void head_quad_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
                                                               const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
                                                               int n_fixed, int V, int M, int d, int64_t ld, int64_t ids_stride,
@@ -218,8 +218,8 @@ __global__ __launch_bounds__(256 * NRG) void head_quad_kernel(const uint16_t* __
   constexpr int HPW = (HI + NRG - 1) / NRG;        // of which each sharing wavefront fetches this many
   constexpr int RPG = 4 * RT;                      // rows per row group
   constexpr int NOUT = RT * MT * 16;               // outputs per row group
-  static_assert(HI <= 16 && NOUT * 4 * NRG * 4 <= 4 * HI * 1024, "LDS budget");
-  __shared__ __attribute__((aligned(16))) char hs[4 * HI * 1024];
+  static_assert(HI <= 16, "LDS budget");
+  extern __shared__ __attribute__((aligned(16))) char hs[];   // 4*HI KB of hidden-row operands, then the K-quarter sums
   const int b = blockIdx.z;
   const int lane = threadIdx.x & 63;
   const int w = threadIdx.x >> 6;
@@ -269,7 +269,8 @@ __global__ __launch_bounds__(256 * NRG) void head_quad_kernel(const uint16_t* __
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[rt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  for (int kb = 0; kb < d; kb += 512 * KS) {
+  // ONEK: d <= 512*KS, one K-iteration, straight-line code
+  for (int kb = 0; kb < (ONEK ? 1 : d); kb += 512 * KS) {
     if (kb != 0) load_h(kb, hv);
     u32x4 wv[RT][KS];
 #pragma unroll
@@ -297,8 +298,7 @@ __global__ __launch_bounds__(256 * NRG) void head_quad_kernel(const uint16_t* __
 
   // result lane l holds product rows 4*(l/16)+v, column l%16: the diagonal block entry is v == l%4;
   // the four parts sit in the four lanes of a quad
-  __syncthreads();                                          // hs is reused for the K-quarter sums
-  float* red = reinterpret_cast<float*>(hs);
+  float* red = reinterpret_cast<float*>(hs + 4 * HI * 1024);
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
@@ -326,8 +326,22 @@ static hipError_t run_quad(const uint16_t* W, const uint16_t* H, const int32_t* 
                            int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride,
                            float* logits, hipStream_t s) {
   constexpr int ROWS = 4 * RT * NRG;
+  constexpr int LDS = 4 * MT * KS * 1024 + 4 * NRG * (RT * MT * 16) * 4;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_quad_kernel<NRG, RT, MT, KS, true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_quad_kernel<NRG, RT, MT, KS, false>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
   dim3 grid((cap_rows + ROWS - 1) / ROWS, 1, batch);
-  head_quad_kernel<NRG, RT, MT, KS><<<grid, 256 * NRG, 0, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
+  if (d <= 512 * KS)
+    head_quad_kernel<NRG, RT, MT, KS, true><<<grid, 256 * NRG, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
+  else
+    head_quad_kernel<NRG, RT, MT, KS, false><<<grid, 256 * NRG, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
   return hipGetLastError();
 }
 

@@ -24,7 +24,7 @@ def sources():
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB, *sources()]
+    cmd = [hipcc, *HIPCC_FLAGS, *os.environ.get("NANOSPEC_EXTRA_HIPCC_FLAGS", "").split(), "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB, *sources()]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)

@@ -10,11 +10,12 @@
 // them.  Rows longer than one workgroup's reach are cut into chunks whose winners a second kernel
 // merges the same way.  Values of -inf mark "nothing left" (logits are finite by contract).
 //
-// Fast path in front of the rounds: the k-th largest lane maximum of any one wavefront is a lower
-// bound T on the row's k-th largest value (k lanes of that wavefront hold something >= T), so only
-// elements >= T can be winners.  They are compacted in position order into LDS (typically a few
-// dozen), every thread ranks one candidate against all others, and rank r < k is output slot r.
-// If more than kCandMax elements survive (heavy ties) the kernel falls back to the rounds.
+// Fast path in front of the rounds: the valid runs of a row are split evenly over the wavefronts; if
+// every wavefront reports its ceil(k/NW)-th largest lane maximum, the smallest of those is a lower
+// bound T on the row's k-th largest value (at least k lanes hold something >= T), so only elements
+// >= T can be winners.  They are compacted in position order into LDS (typically one or two dozen),
+// every thread ranks one candidate against all others, and rank r < k is output slot r.  If more
+// than kCandMax elements survive (heavy ties) the kernel falls back to the rounds.
 #include <limits.h>
 
 #include "common.h"
@@ -78,7 +79,14 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
   const int n = n_dev ? n_dev[b] : n_fixed;
   const int64_t row = (int64_t)b * M + m;
   const float* src = logits + row * ld;
-  const int p0 = c * (NW * 64 * EPT) + tid * EPT;            // first position of this lane's run
+  // The valid runs of this chunk are split evenly over the wavefronts (contiguous, in order): every
+  // wavefront sees the same share of the row and position order is still (wavefront, lane, register).
+  const int cbase = c * (NW * 64 * EPT);
+  const int left = n - cbase;
+  const int runs = left > 0 ? (left + EPT - 1) / EPT : 0;
+  int per_wave = (runs + NW - 1) / NW;
+  per_wave = per_wave > 64 ? 64 : per_wave;
+  const int p0 = lane < per_wave ? cbase + (wave * per_wave + lane) * EPT : INT_MAX - EPT;   // first position of this lane's run
 
   float v[EPT];
   if ((ld & 3) == 0) {
@@ -105,7 +113,8 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
 #pragma unroll
     for (int e = 1; e < EPT; ++e) ml = fmaxf(ml, v[e]);
     float x = ml, thr = -INFINITY;
-    for (int r = 0; r < k; ++r) {
+    const int rounds = (k + NW - 1) / NW;                  // NW * rounds >= k lanes hold something >= T
+    for (int r = 0; r < rounds; ++r) {
       thr = wave_max(x);
       const unsigned long long ball = __ballot(x == thr);
       const int L = ball ? __ffsll(ball) - 1 : 0;
@@ -115,7 +124,7 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
     __syncthreads();
     float T = s_thr[0];
 #pragma unroll
-    for (int ww = 1; ww < NW; ++ww) T = fmaxf(T, s_thr[ww]);
+    for (int ww = 1; ww < NW; ++ww) T = fminf(T, s_thr[ww]);
     uint32_t flags = 0;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) flags |= (uint32_t)((p0 + e < n) && (v[e] >= T)) << e;
@@ -174,7 +183,7 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
     }
   }
   // ---- general path: k rounds per wavefront, then over the wavefronts' winners
-  const int wbase = c * (NW * 64 * EPT) + wave * (64 * EPT);
+  const int wbase = cbase + wave * per_wave * EPT;
   wave_select<EPT>(v, k, lane, [&](int r, float val, int pos) {
     if (lane == 0) {
       s_val[wave * k + r] = val;

@@ -117,6 +117,19 @@ NANOSPEC_API nanospec_status nanospec_vocab_init(nanospec_state* st, const int32
 NANOSPEC_API nanospec_status nanospec_vocab_update(nanospec_state* st, const int32_t* d_new_ids, const int32_t* h_new_off,
                                       const int32_t* d_topk_ids, const int32_t* h_topk_off, void* hip_stream);
 
+/* Stream update with the candidate set built on the device, Eq. 3 for C_draft ("the set of all
+ * unique token indices present anywhere in the generated draft tree", Sec. 3.2): for sequence b the ids
+ * d_cand_ids[b*cand_stride .. +cand_per_seq) -- typically the [M][k] output of nanospec_topk_remap of the
+ * same state, passed without a host round trip -- are de-duplicated and appended to the stream in
+ * ascending id order (the paper leaves the order of tuple(set) open), then Eq. 4 as in
+ * nanospec_vocab_update.  The number of ids appended is known only on the device.  Entries equal to -1
+ * (top-k padding) are skipped; other ids outside [0,V) are skipped and raise NANOSPEC_DEV_BAD_ID.  T is kept.
+ *   d_cand_ids : device int32 [batch][cand_stride]; cand_per_seq <= m_cap * k_cap.
+ * Errors: EINVAL (null, negative, stride < count), ECAPACITY.  Asynchronous; takes no host integers that
+ * change from step to step, so one recorded HIP graph of a whole draft step can be replayed indefinitely. */
+NANOSPEC_API nanospec_status nanospec_vocab_append_unique(nanospec_state* st, const int32_t* d_cand_ids,
+                                                          int32_t cand_per_seq, int64_t cand_stride, void* hip_stream);
+
 /* Borrowed device views of the active vocabulary, valid until nanospec_destroy; contents are
  * valid in stream order after the last init/update.
  *   *d_ids : int32[batch][capacity], row b holds I of sequence b ascending in [0, n_b)

@@ -42,6 +42,7 @@ def _lib(omp: bool = False) -> C.CDLL:
         L.oracle_vocab_free.argtypes = [C.c_void_p]
         L.oracle_vocab_init.argtypes = [C.c_void_p, i32p, C.c_int64, i32p, C.c_int64]
         L.oracle_vocab_update.argtypes = [C.c_void_p, i32p, C.c_int64, C.c_int32, i32p, C.c_int64]
+        L.oracle_vocab_append_unique.argtypes = [C.c_void_p, i32p, C.c_int64]
         L.oracle_vocab_stream_len.restype = C.c_int64
         L.oracle_vocab_stream_len.argtypes = [C.c_void_p]
         L.oracle_vocab_active.restype = C.c_int64
@@ -83,6 +84,10 @@ class Vocab:
         t = _i32(topk) if topk is not None else np.zeros(0, np.int32)
         self._L.oracle_vocab_update(self._h, _p(new_ids, C.c_int32), len(new_ids), int(topk is not None),
                                     _p(t, C.c_int32), len(t))
+
+    def append_unique(self, cand):
+        cand = _i32(np.asarray(cand).ravel())
+        self._L.oracle_vocab_append_unique(self._h, _p(cand, C.c_int32), len(cand))
 
     def stream_len(self) -> int:
         return int(self._L.oracle_vocab_stream_len(self._h))

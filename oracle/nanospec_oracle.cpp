@@ -81,6 +81,17 @@ void oracle_vocab_update(void* h, const int32_t* new_ids, int64_t n_new, int32_t
   }
 }
 
+// Eq. 3 for a candidate *set* (C_draft: all unique token indices of the draft tree): the distinct
+// valid ids are appended in ascending order (the paper leaves the order of tuple(set) open); -1 entries
+// are padding.
+void oracle_vocab_append_unique(void* h, const int32_t* cand, int64_t n_cand) {
+  Vocab* v = static_cast<Vocab*>(h);
+  std::set<int32_t> C;
+  for (int64_t i = 0; i < n_cand; ++i)
+    if (cand[i] >= 0 && cand[i] < v->V) C.insert(cand[i]);
+  v->S.insert(v->S.end(), C.begin(), C.end());
+}
+
 int64_t oracle_vocab_stream_len(void* h) { return static_cast<int64_t>(static_cast<Vocab*>(h)->S.size()); }
 
 // Eq. 4: I = Unique(Suffix(S, W_max)) U T, ascending.  Returns |I|; writes at most cap ids.

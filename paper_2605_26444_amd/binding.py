@@ -21,7 +21,7 @@ MAX_BATCH = 256
 
 EXPORTS = [
     "nanospec_status_string", "nanospec_state_layout", "nanospec_create", "nanospec_destroy",
-    "nanospec_vocab_init", "nanospec_vocab_update", "nanospec_vocab_view", "nanospec_sparse_head",
+    "nanospec_vocab_init", "nanospec_vocab_update", "nanospec_vocab_append_unique", "nanospec_vocab_view", "nanospec_sparse_head",
     "nanospec_topk_remap", "nanospec_dense_head", "nanospec_dense_topk_workspace", "nanospec_dense_topk",
     "nanospec_last_device_error",
 ]
@@ -59,6 +59,7 @@ def lib() -> C.CDLL:
         L.nanospec_destroy.argtypes = [vp]
         L.nanospec_vocab_init.argtypes = [vp, vp, i32p, vp, i32p, vp]
         L.nanospec_vocab_update.argtypes = [vp, vp, i32p, vp, i32p, vp]
+        L.nanospec_vocab_append_unique.argtypes = [vp, vp, i32, i64, vp]
         L.nanospec_vocab_view.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), i32p]
         L.nanospec_sparse_head.argtypes = [vp, vp, vp, i32, vp, vp]
         L.nanospec_topk_remap.argtypes = [vp, vp, i32, i32, vp, vp, vp]
@@ -133,6 +134,12 @@ def nanospec_vocab_update(st, d_new_ids, h_new_off, d_topk_ids=None, h_topk_off=
     a, ap = _off(h_new_off)
     b, bp = _off(h_topk_off)
     _check(lib().nanospec_vocab_update(st, _ptr(d_new_ids), ap, _ptr(d_topk_ids), bp, _stream(stream)), "nanospec_vocab_update")
+
+
+def nanospec_vocab_append_unique(st, d_cand_ids, cand_per_seq, cand_stride=None, stream=None):
+    stride = cand_per_seq if cand_stride is None else cand_stride
+    _check(lib().nanospec_vocab_append_unique(st, _ptr(d_cand_ids), cand_per_seq, stride, _stream(stream)),
+           "nanospec_vocab_append_unique")
 
 
 def nanospec_vocab_view(st):

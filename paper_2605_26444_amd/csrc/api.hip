@@ -169,6 +169,14 @@ nanospec_status nanospec_vocab_update(nanospec_state* st, const int32_t* d_new_i
   return vocab_call(st, d_new_ids, h_new_off, d_topk_ids, h_topk_off, false, hip_stream);
 }
 
+nanospec_status nanospec_vocab_append_unique(nanospec_state* st, const int32_t* d_cand_ids, int32_t cand_per_seq,
+                                             int64_t cand_stride, void* hip_stream) {
+  if (!st || cand_per_seq < 0 || (cand_per_seq > 0 && !d_cand_ids) || cand_stride < cand_per_seq) return NANOSPEC_EINVAL;
+  if (cand_per_seq > st->unique_cap) return NANOSPEC_ECAPACITY;
+  hipError_t e = launch_vocab_append_unique(st, d_cand_ids, cand_per_seq, cand_stride, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;
+}
+
 nanospec_status nanospec_vocab_view(const nanospec_state* st, const int32_t** d_ids, const int32_t** d_n,
                                     int32_t* capacity) {
   if (!st) return NANOSPEC_EINVAL;

@@ -43,7 +43,7 @@ struct nanospec_state {
   char* topk_ws;            // two-pass top-k candidates
   int64_t partial_bytes, topk_ws_bytes;
   int32_t* h_err_pinned;    // pinned host word for reading the device flags
-  int vocab_lds_bytes;
+  int vocab_lds_bytes, unique_lds_bytes, unique_cap;
 };
 
 namespace nanospec {
@@ -53,6 +53,8 @@ hipError_t launch_vocab_clear(const nanospec_state* st, hipStream_t s);
 hipError_t launch_vocab_apply(const nanospec_state* st, const int32_t* d_new, const Offsets& noff,
                               const int32_t* d_topk, const Offsets& toff, int replace_T, hipStream_t s);
 hipError_t vocab_configure(nanospec_state* st);
+hipError_t launch_vocab_append_unique(const nanospec_state* st, const int32_t* d_cand, int per_seq, int64_t stride,
+                                      hipStream_t s);
 
 // head.hip
 // logits[b][m][j] for j < n_b (n read on the device).  ids == nullptr: identity list of n_fixed rows.

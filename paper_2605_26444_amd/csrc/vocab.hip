@@ -39,29 +39,51 @@ __device__ __forceinline__ int wave_incl_scan(int x, int lane) {
   return x;
 }
 
-__global__ __launch_bounds__(kVocabThreads) void vocab_apply_kernel(VocabPtrs p, const int32_t* __restrict__ new_ids,
-                                                                    Offsets noff, const int32_t* __restrict__ topk,
-                                                                    Offsets toff, int replace_T) {
-  extern __shared__ uint32_t lds[];
-  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int nwords = p.nwords, V = p.V, W = p.window;
-  uint32_t* wb = lds;
-  uint32_t* tb = lds + nwords;
-  int* sc = reinterpret_cast<int*>(tb + nwords);   // 16 wave totals
+// Ascending compaction of a bitmap held in LDS: popcount per thread, workgroup exclusive scan,
+// emission in id order.  word(i) yields bitmap word i; out[0..total) receives the ids (at most cap
+// are stored).  Every thread of the workgroup must call it, after a barrier that separates it from
+// any earlier use of sc; returns the number of set bits.
+template <typename WordFn>
+__device__ __forceinline__ int compact_bitmap(WordFn word, int nwords, int32_t* out, int cap, int* sc, int tid) {
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wpt = (((nwords + kVocabThreads - 1) / kVocabThreads) + 3) & ~3;
+  const int w0 = tid * wpt;
+  int mine = 0;
+  for (int i = w0; i < w0 + wpt && i < nwords; ++i) mine += __popc(word(i));
+  const int incl = wave_incl_scan(mine, lane);
+  if (lane == 63) sc[wave] = incl;
+  __syncthreads();
+  int off = incl - mine, total = 0;
+  for (int w = 0; w < kVocabThreads / 64; ++w) {
+    const int t = sc[w];
+    if (w < wave) off += t;
+    total += t;
+  }
+  for (int i = w0; i < w0 + wpt && i < nwords; ++i) {
+    uint32_t x = word(i);
+    while (x) {
+      const int bit = __ffs(x) - 1;
+      if (off < cap) out[off] = i * 32 + bit;
+      ++off;
+      x &= x - 1;
+    }
+  }
+  return total;
+}
 
+// One stream update of sequence b (Eq. 3 then Eq. 4): append src[0..a), evict what leaves the window,
+// optionally replace T, rebuild the ascending active list.  wb/tb are the LDS copies of the bitmaps
+// (already loaded, any barrier needed to see them is the caller's), sc 16 ints of LDS scratch.
+__device__ __forceinline__ void vocab_apply_body(const VocabPtrs& p, int b, const int32_t* src, int a,
+                                                 const int32_t* ts, int nt, int replace_T, uint32_t* wb, uint32_t* tb,
+                                                 int* sc, int bad) {
+  const int tid = threadIdx.x;
+  const int nwords = p.nwords, V = p.V, W = p.window;
   uint32_t* gw = p.wbit + (size_t)b * nwords;
   uint32_t* gt = p.tbit + (size_t)b * nwords;
   uint32_t* cnt = p.cnt + (size_t)b * V;
   int32_t* ring = p.ring + (size_t)b * W;
 
-  // bitmaps -> LDS
-  for (int i = tid * 4; i < nwords; i += kVocabThreads * 4) {
-    *reinterpret_cast<uint4*>(wb + i) = *reinterpret_cast<const uint4*>(gw + i);
-    *reinterpret_cast<uint4*>(tb + i) = replace_T ? make_uint4(0, 0, 0, 0) : *reinterpret_cast<const uint4*>(gt + i);
-  }
-
-  const int a = noff.v[b + 1] - noff.v[b];
-  const int32_t* src = new_ids + noff.v[b];
   const int pos = p.pos[b], fill = p.fill[b];
   const int skip = a > W ? a - W : 0;      // ids that enter and leave the window within this call
   const int ae = a - skip;
@@ -69,7 +91,6 @@ __global__ __launch_bounds__(kVocabThreads) void vocab_apply_kernel(VocabPtrs p,
   if (n_evict < 0) n_evict = 0;
   int oldest = pos - fill;
   if (oldest < 0) oldest += W;
-  int bad = 0;
 
   // Leaving ids first: -1 on the counter with a returning atomic; the decrement that brings a
   // counter to zero (whichever thread performs it) clears the window bit.  Entering ids get their +1
@@ -102,8 +123,6 @@ __global__ __launch_bounds__(kVocabThreads) void vocab_apply_kernel(VocabPtrs p,
     ring[slot] = ok ? v : -1;
   }
   if (replace_T) {
-    const int nt = toff.v[b + 1] - toff.v[b];
-    const int32_t* ts = topk + toff.v[b];
     for (int i = tid; i < nt; i += kVocabThreads) {
       const int t = ts[i];
       if ((unsigned)t < (unsigned)V) atomicOr(&tb[t >> 5], 1u << (t & 31));
@@ -112,30 +131,8 @@ __global__ __launch_bounds__(kVocabThreads) void vocab_apply_kernel(VocabPtrs p,
   }
   __syncthreads();
 
-  // compaction of (window | T): popcount per thread, workgroup exclusive scan, ascending emission
-  const int wpt = (((nwords + kVocabThreads - 1) / kVocabThreads) + 3) & ~3;
-  const int w0 = tid * wpt;
-  int mine = 0;
-  for (int i = w0; i < w0 + wpt && i < nwords; ++i) mine += __popc(wb[i] | tb[i]);
-  const int incl = wave_incl_scan(mine, lane);
-  if (lane == 63) sc[wave] = incl;
-  __syncthreads();
-  int off = incl - mine, total = 0;
-  for (int w = 0; w < kVocabThreads / 64; ++w) {
-    const int t = sc[w];
-    if (w < wave) off += t;
-    total += t;
-  }
-  int32_t* ids = p.ids + (size_t)b * p.cap;
-  for (int i = w0; i < w0 + wpt && i < nwords; ++i) {
-    uint32_t x = wb[i] | tb[i];
-    while (x) {
-      const int bit = __ffs(x) - 1;
-      if (off < p.cap) ids[off] = i * 32 + bit;
-      ++off;
-      x &= x - 1;
-    }
-  }
+  // compaction of (window | T)
+  const int total = compact_bitmap([&](int i) { return wb[i] | tb[i]; }, nwords, p.ids + (size_t)b * p.cap, p.cap, sc, tid);
   // bitmaps back to HBM
   for (int i = tid * 4; i < nwords; i += kVocabThreads * 4) {
     *reinterpret_cast<uint4*>(gw + i) = *reinterpret_cast<const uint4*>(wb + i);
@@ -152,13 +149,72 @@ __global__ __launch_bounds__(kVocabThreads) void vocab_apply_kernel(VocabPtrs p,
   if (bad) atomicOr(p.err, (int)NANOSPEC_DEV_BAD_ID);
 }
 
+__device__ __forceinline__ void load_bitmaps(const VocabPtrs& p, int b, uint32_t* wb, uint32_t* tb, int replace_T) {
+  const uint32_t* gw = p.wbit + (size_t)b * p.nwords;
+  const uint32_t* gt = p.tbit + (size_t)b * p.nwords;
+  for (int i = threadIdx.x * 4; i < p.nwords; i += kVocabThreads * 4) {
+    *reinterpret_cast<uint4*>(wb + i) = *reinterpret_cast<const uint4*>(gw + i);
+    *reinterpret_cast<uint4*>(tb + i) = replace_T ? make_uint4(0, 0, 0, 0) : *reinterpret_cast<const uint4*>(gt + i);
+  }
+}
+
+__global__ __launch_bounds__(kVocabThreads) void vocab_apply_kernel(VocabPtrs p, const int32_t* __restrict__ new_ids,
+                                                                    Offsets noff, const int32_t* __restrict__ topk,
+                                                                    Offsets toff, int replace_T) {
+  extern __shared__ uint32_t lds[];
+  const int b = blockIdx.x;
+  uint32_t* wb = lds;
+  uint32_t* tb = lds + p.nwords;
+  int* sc = reinterpret_cast<int*>(tb + p.nwords);   // 16 wave totals
+  load_bitmaps(p, b, wb, tb, replace_T);
+  vocab_apply_body(p, b, new_ids + noff.v[b], noff.v[b + 1] - noff.v[b], topk + toff.v[b], toff.v[b + 1] - toff.v[b],
+                   replace_T, wb, tb, sc, 0);
+}
+
+// Eq. 3 with the candidate set built on the device: the ids of cand[b][0..per_seq) (for instance the
+// top-k ids of all draft-tree nodes, straight from nanospec_topk_remap's output) are de-duplicated
+// through a scratch bitmap in LDS and appended to the stream of sequence b in ascending id order;
+// how many are appended is known only on the device.  Entries equal to -1 (top-k padding) are
+// skipped; other ids outside [0,V) are skipped and flagged.  T is kept.
+__global__ __launch_bounds__(kVocabThreads) void vocab_append_unique_kernel(VocabPtrs p, const int32_t* __restrict__ cand,
+                                                                            int per_seq, int64_t stride, int ucap) {
+  extern __shared__ uint32_t lds[];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int nwords = p.nwords;
+  uint32_t* wb = lds;
+  uint32_t* tb = lds + nwords;
+  int* sc = reinterpret_cast<int*>(tb + nwords);
+  uint32_t* ub = reinterpret_cast<uint32_t*>(sc + 32);
+  int32_t* ulist = reinterpret_cast<int32_t*>(ub + nwords);
+  load_bitmaps(p, b, wb, tb, 0);
+  for (int i = tid * 4; i < nwords; i += kVocabThreads * 4) *reinterpret_cast<uint4*>(ub + i) = make_uint4(0, 0, 0, 0);
+  __syncthreads();
+  int bad = 0;
+  for (int i = tid; i < per_seq; i += kVocabThreads) {
+    const int v = cand[b * stride + i];
+    if ((unsigned)v < (unsigned)p.V) atomicOr(&ub[v >> 5], 1u << (v & 31));
+    else if (v != -1) bad = 1;
+  }
+  __syncthreads();
+  int a = compact_bitmap([&](int i) { return ub[i]; }, nwords, ulist, ucap, sc, tid);
+  a = a < ucap ? a : ucap;
+  __syncthreads();
+  vocab_apply_body(p, b, ulist, a, nullptr, 0, 0, wb, tb, sc, bad);
+}
+
 hipError_t vocab_configure(nanospec_state* st) {
   st->vocab_lds_bytes = (2 * st->vp.nwords + 32) * 4;
-  if (st->vocab_lds_bytes > 160 * 1024 - 512) return hipErrorInvalidValue;
+  st->unique_cap = st->m_cap * st->k_cap;
+  st->unique_lds_bytes = (3 * st->vp.nwords + 32 + st->unique_cap) * 4;
+  if (st->unique_lds_bytes > 160 * 1024 - 512) return hipErrorInvalidValue;
+  hipError_t e = hipSuccess;
   if (st->vocab_lds_bytes > 48 * 1024)
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(vocab_apply_kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, st->vocab_lds_bytes);
-  return hipSuccess;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(vocab_apply_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            st->vocab_lds_bytes);
+  if (e == hipSuccess && st->unique_lds_bytes > 48 * 1024)
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(vocab_append_unique_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, st->unique_lds_bytes);
+  return e;
 }
 
 hipError_t launch_vocab_clear(const nanospec_state* st, hipStream_t s) {
@@ -173,6 +229,13 @@ hipError_t launch_vocab_apply(const nanospec_state* st, const int32_t* d_new, co
                               const int32_t* d_topk, const Offsets& toff, int replace_T, hipStream_t s) {
   vocab_apply_kernel<<<st->batch, kVocabThreads, st->vocab_lds_bytes, s>>>(st->vp, d_new, noff, d_topk, toff,
                                                                            replace_T);
+  return hipGetLastError();
+}
+
+hipError_t launch_vocab_append_unique(const nanospec_state* st, const int32_t* d_cand, int per_seq, int64_t stride,
+                                      hipStream_t s) {
+  vocab_append_unique_kernel<<<st->batch, kVocabThreads, st->unique_lds_bytes, s>>>(st->vp, d_cand, per_seq, stride,
+                                                                                  st->unique_cap);
   return hipGetLastError();
 }
 

@@ -354,3 +354,64 @@ def test_head_shapes_against_oracle(d, M, n_ctx, batch):
         o32, o64 = oracle.head(W, H[b], ids=act[b], omp=True)
         assert_logits_close(g[b, :, :n], o64, o32, f"d={d} M={M} seq {b}")
     st.close()
+
+
+def test_device_side_feedback_loop():
+    """Eq. 3 closed on the device: the top-k ids of every draft node go straight from nanospec_topk_remap's
+    output into the stream (de-duplicated, ascending) with no host integers; recorded once as a HIP graph and
+    replayed.  Checked every step: the active set against the oracle fed with the GPU's own top-k ids, and the
+    top-k ids against the oracle's selection on the GPU's logits."""
+    cfg = synth.CONFIGS["c1"]
+    W = host_W(cfg)
+    V, d, M, k = cfg["V"], cfg["d"], cfg["M"], cfg["k"]
+    dW = dev_bf16(W)
+    seqs = synth.make_sequences(cfg)
+    for batch, window in ((1, 64), (3, 300)):
+        st = B.State(V, d, batch, window, seqs["topk_cap"], M, k)
+        orc = [oracle.Vocab(V, window) for _ in range(batch)]
+        ctx = [seqs["ctx"][0][37 * b: 37 * b + 200] for b in range(batch)]
+        T0 = [seqs["T0"][0][: 100 + 50 * b] for b in range(batch)]
+        f, off = csr(ctx)
+        tf, toff = csr(T0)
+        B.nanospec_vocab_init(st.h, dev(f), off, dev(tf), toff)
+        for b in range(batch):
+            orc[b].init(ctx[b], T0[b])
+        cap = st.capacity
+        H = synth.make_H(cfg, 11, batch, M)
+        dH = dev_bf16(H)
+        logits = torch.empty((batch, M, cap), dtype=torch.float32, device="cuda")
+        oi = torch.full((batch, M, k), -1, dtype=torch.int32, device="cuda")
+        ov = torch.empty((batch, M, k), dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            cs = torch.cuda.current_stream().cuda_stream
+            B.nanospec_vocab_append_unique(st.h, oi, M * k, M * k, cs)       # ids of the previous step
+            B.nanospec_sparse_head(st.h, dW, dH, M, logits, cs)
+            B.nanospec_topk_remap(st.h, logits, M, k, oi, ov, cs)
+        prev = oi.cpu().numpy().copy()                                       # all -1: nothing appended in step 0
+        for step in range(12):
+            g.replay()
+            torch.cuda.synchronize()
+            act = st.read_active()
+            gl, gi = logits.cpu().numpy(), oi.cpu().numpy()
+            for b in range(batch):
+                orc[b].append_unique(prev[b])
+                exp = orc[b].active()
+                assert np.array_equal(act[b], exp), (batch, step, b)
+                for m in range(M):
+                    ei, _ = oracle.topk(gl[b, m, :len(exp)], exp, k)
+                    assert np.array_equal(gi[b, m], ei), (batch, step, b, m)
+            prev = gi.copy()
+            if step == 5:                                                     # eager call between replays: bad ids
+                junk = dev(np.array([[V, -1, -7, 5] + [-1] * (M * k - 4)] * batch, np.int32))
+                B.nanospec_vocab_append_unique(st.h, junk, M * k, M * k)
+                for b in range(batch):
+                    orc[b].append_unique([5])
+                assert B.nanospec_last_device_error(st.h) == B.DEV_BAD_ID
+        assert B.nanospec_last_device_error(st.h) == 0
+        import ctypes as C
+        assert B.lib().nanospec_vocab_append_unique(st.h, oi.data_ptr(), M * k + 1, M * k + 1, None) == B.ECAPACITY
+        assert B.lib().nanospec_vocab_append_unique(st.h, None, 4, 4, None) == B.EINVAL
+        assert B.lib().nanospec_vocab_append_unique(st.h, oi.data_ptr(), 4, 2, None) == B.EINVAL
+        st.close()

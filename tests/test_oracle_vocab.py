@@ -157,3 +157,19 @@ def test_window_bound_paper_setting():
     for _ in range(5):
         v.update(rng.integers(0, 128256, size=2000))
         assert len(v.active()) <= 3072
+
+
+def test_append_unique_is_a_sorted_set_append():
+    """Eq. 3 with a candidate set: distinct valid ids, ascending, -1 padding and bad ids dropped."""
+    v = oracle.Vocab(100, 4)
+    v.init([50, 51])
+    v.append_unique([7, 3, 7, -1, 3, 99, 100, 250])
+    assert v.stream_len() == 5                          # 3, 7, 99 appended
+    assert v.active().tolist() == [3, 7, 51, 99]        # window 4: 51, 3, 7, 99
+    w = oracle.Vocab(100, 4)
+    w.init([50, 51])
+    w.update([3, 7, 99])                                # the same thing through the plain append
+    assert w.active().tolist() == v.active().tolist()
+    v.append_unique([])
+    v.append_unique([-1, -1])
+    assert v.stream_len() == 5

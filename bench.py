@@ -170,6 +170,22 @@ def main():
     upd_us = train(lambda i, cs: B.nanospec_vocab_update(st.h, d_new, zero_off, None, None, cs))
     topk_us = train(lambda i, cs: B.nanospec_topk_remap(st.h, logits, M, k, out_ids, out_vals, cs))
 
+    # closed loop on the device (Eq. 3 for C_draft): every step feeds the previous step's top-k ids of all M
+    # nodes back into the stream with nanospec_vocab_append_unique -- no host integers at all
+    def loop_step(s, cs):
+        B.nanospec_vocab_append_unique(st.h, out_ids, M * k, M * k, cs)
+        B.nanospec_sparse_head(st.h, Wd[s % R], Hd[s % NH], M, logits, cs)
+        B.nanospec_topk_remap(st.h, logits, M, k, out_ids, out_vals, cs)
+    for s in range(20):
+        loop_step(s, stream)
+    torch.cuda.synchronize()
+    KL = min(K, 1000)
+    loop_ms = timed(loop_step, 0, KL)
+    app_us = train(lambda i, cs: B.nanospec_vocab_append_unique(st.h, out_ids, M * k, M * k, cs))
+    n_loop = [len(a) for a in st.read_active()]
+    closed = {"steps_per_s": round(KL / (loop_ms * 1e-3), 1), "us_per_step": round(loop_ms * 1e3 / KL, 2),
+              "append_unique_us": round(app_us, 2), "active_after": n_loop[0]}
+
     # dense comparison point: full-vocabulary head + top-k over V
     dense = None
     if not args.no_dense:
@@ -224,6 +240,7 @@ def main():
                          round(PMC_TRAFFIC_PER_ROW[args.config] * n_sum) if args.config in PMC_TRAFFIC_PER_ROW else None),
                      "bytes_per_launch": alg_bytes, "us_per_launch": round(head_us, 3)},
         "kernels_us": {"vocab_update": round(upd_us, 2), "sparse_head": round(head_us, 2), "topk_remap": round(topk_us, 2)},
+        "closed_loop": closed,
         "dense": dense,
         "cpu_baseline": cpu,
         "setup_s": round(time.time() - t0, 1),

@@ -117,8 +117,8 @@ NANOSPEC_API nanospec_status nanospec_vocab_init(nanospec_state* st, const int32
 NANOSPEC_API nanospec_status nanospec_vocab_update(nanospec_state* st, const int32_t* d_new_ids, const int32_t* h_new_off,
                                       const int32_t* d_topk_ids, const int32_t* h_topk_off, void* hip_stream);
 
-/* Stream update with the candidate set built on the device, Eq. 3 for C_draft ("the set of all
- * unique token indices present anywhere in the generated draft tree", Sec. 3.2): for sequence b the ids
+/* Stream update with the candidate set built on the device, Eq. 3 for C_draft (Sec. 3.2: every distinct
+ * token id that occurs in the step's draft tree, accepted or not): for sequence b the ids
  * d_cand_ids[b*cand_stride .. +cand_per_seq) -- typically the [M][k] output of nanospec_topk_remap of the
  * same state, passed without a host round trip -- are de-duplicated and appended to the stream in
  * ascending id order (the paper leaves the order of tuple(set) open), then Eq. 4 as in

@@ -49,6 +49,7 @@ def _lib(omp: bool = False) -> C.CDLL:
         L.oracle_vocab_active.argtypes = [C.c_void_p, i32p, C.c_int64]
         L.oracle_head.argtypes = [u16p, u16p, i32p, C.c_int64, C.c_int32, C.c_int32, C.c_int64, f32p, f64p]
         L.oracle_topk.argtypes = [f32p, i32p, C.c_int64, C.c_int32, i32p, f32p]
+        L.oracle_log_softmax.argtypes = [f32p, C.c_int64, f64p]
         L.oracle_max_threads.restype = C.c_int32
         _loaded[omp] = L
     return _loaded[omp]
@@ -132,6 +133,28 @@ def topk(vals, ids, k: int):
     ov = np.empty(k, dtype=np.float32)
     _lib().oracle_topk(_p(vals, C.c_float), _p(ids, C.c_int32), n, k, _p(oi, C.c_int32), _p(ov, C.c_float))
     return oi, ov
+
+
+def log_softmax(vals):
+    """Log-probabilities of one logit row renormalised over its own entries (Sec. 4.2): float64[n]."""
+    vals = np.ascontiguousarray(vals, dtype=np.float32)
+    out = np.empty(len(vals), dtype=np.float64)
+    _lib().oracle_log_softmax(_p(vals, C.c_float), len(vals), _p(out, C.c_double))
+    return out
+
+
+def topk_logprob(vals, ids, k: int):
+    """Top-k of one row with the values replaced by log-probabilities over the active set:
+    (ids int32[k], logp float64[k]); slots beyond the row length get id -1 and -inf."""
+    oi, ov = topk(vals, ids, k)
+    lp = log_softmax(vals)
+    # the selected values are looked up by position: lowest position among equal (value, id) is irrelevant for logp
+    out = np.full(k, -np.inf, dtype=np.float64)
+    vals = np.asarray(vals, dtype=np.float32)
+    for r in range(min(k, len(vals))):
+        j = int(np.flatnonzero(vals == ov[r])[0])
+        out[r] = lp[j]
+    return oi, out
 
 
 def max_threads() -> int:

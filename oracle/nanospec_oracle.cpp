@@ -14,6 +14,7 @@
 //   * Dense head  (Eq. 1): the same loop over all V rows.
 //   * Top-k + remap (Alg. 1 "SelectDraftTokens(z', I)", operator T_K of Sec. 3.2): full sort of
 //       (value, global id) by value descending then id ascending; the first k.
+//   * Log-softmax over the active set (Sec. 4.2, the renormalised draft distribution): fp64.
 //
 // Readings where the paper is silent are listed in the repository's design notes; in short:
 // ids are 0-based; the active list is in ascending id order; top-k ties go to the lower id;
@@ -23,6 +24,7 @@
 // Parity status: every function here is pinned by tests/test_oracle_*.py (brute force on tiny
 // inputs, closed forms, invariants, independent float64 library matmul, hand-worked cases).
 #include <algorithm>
+#include <cmath>
 #include <cstdint>
 #include <cstring>
 #include <limits>
@@ -151,6 +153,19 @@ void oracle_topk(const float* vals, const int32_t* ids, int64_t n, int32_t k, in
       out_vals[r] = -std::numeric_limits<float>::infinity();
     }
   }
+}
+
+// Draft distribution on the pruned vocabulary (Sec. 4.2: with the irrelevant tokens gone, the softmax is
+// renormalised over the active set only): logp[j] = z[j] - log(sum_i exp(z[i])), i over the n active
+// entries, in fp64, the sum taken after subtracting the largest logit.  n == 0 leaves nothing to write.
+void oracle_log_softmax(const float* vals, int64_t n, double* out_logp) {
+  if (n <= 0) return;
+  double zmax = vals[0];
+  for (int64_t j = 1; j < n; ++j) zmax = std::max(zmax, static_cast<double>(vals[j]));
+  double sum = 0.0;
+  for (int64_t j = 0; j < n; ++j) sum += std::exp(static_cast<double>(vals[j]) - zmax);
+  const double lse = zmax + std::log(sum);
+  for (int64_t j = 0; j < n; ++j) out_logp[j] = static_cast<double>(vals[j]) - lse;
 }
 
 int32_t oracle_max_threads(void) {

@@ -388,11 +388,13 @@ __global__ __launch_bounds__(256) void head_tile64_kernel(const uint16_t* __rest
   const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
   char* reg = smem + w * (16 * STRB);
 
-  // one id per lane (capacity-bounded, not waiting for the row count), handed out by readlane;
-  // no early exit: it would let the hidden-row loads sink below the wait for the count
+  // one id per lane (capacity-bounded, not waiting for the row count), handed out by readlane
   int myid = j0 + (lane & 15);
   if (ids) myid = ids[b * ids_stride + j0 + (lane & 15)];
   const int n = n_dev ? n_dev[b] : n_fixed;
+  // split-K launches are sized by capacity: tiles past n leave before they pull their hidden-row slice
+  // (measured neutral at n close to capacity, and it spares the L2 when n is far below it)
+  if (!LOOPK && (int)blockIdx.x * 64 >= n) return;
   u32x4 hv[16], wv[16];
   auto load_slice = [&](int sl) {
     const int c = sl * 512 + lane * 8;
@@ -461,8 +463,16 @@ __global__ __launch_bounds__(256) void head_splitk_reduce_kernel(const float* __
   if (j >= n_dev[b]) return;
   const int64_t plane = (int64_t)batch * M * cap;
   const float* p = partial + ((int64_t)b * M + m) * cap + j;
-  f32x4 s = *reinterpret_cast<const f32x4*>(p);
-  for (int sl = 1; sl < S; ++sl) s += *reinterpret_cast<const f32x4*>(p + sl * plane);
+  // eight planes are fetched before the first add so that their latencies overlap; the adds keep slice order
+  f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int s0 = 0; s0 < S; s0 += 8) {
+    f32x4 v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      v[i] = s0 + i < S ? *reinterpret_cast<const f32x4*>(p + (s0 + i) * plane) : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += v[i];
+  }
   *reinterpret_cast<f32x4*>(logits + ((int64_t)b * M + m) * ld + j) = s;
 }
 

@@ -171,20 +171,22 @@ def main():
     topk_us = train(lambda i, cs: B.nanospec_topk_remap(st.h, logits, M, k, out_ids, out_vals, cs))
 
     # closed loop on the device (Eq. 3 for C_draft): every step feeds the previous step's top-k ids of all M
-    # nodes back into the stream with nanospec_vocab_append_unique -- no host integers at all
+    # nodes back into the stream with nanospec_vocab_append_unique -- no host integers at all -- and the
+    # selection returns log-probabilities renormalised over the active set (Sec. 4.2)
     def loop_step(s, cs):
         B.nanospec_vocab_append_unique(st.h, out_ids, M * k, M * k, cs)
         B.nanospec_sparse_head(st.h, Wd[s % R], Hd[s % NH], M, logits, cs)
-        B.nanospec_topk_remap(st.h, logits, M, k, out_ids, out_vals, cs)
+        B.nanospec_topk_logprob_remap(st.h, logits, M, k, out_ids, out_vals, cs)
     for s in range(20):
         loop_step(s, stream)
     torch.cuda.synchronize()
     KL = min(K, 1000)
     loop_ms = timed(loop_step, 0, KL)
     app_us = train(lambda i, cs: B.nanospec_vocab_append_unique(st.h, out_ids, M * k, M * k, cs))
+    lp_us = train(lambda i, cs: B.nanospec_topk_logprob_remap(st.h, logits, M, k, out_ids, out_vals, cs))
     n_loop = [len(a) for a in st.read_active()]
     closed = {"steps_per_s": round(KL / (loop_ms * 1e-3), 1), "us_per_step": round(loop_ms * 1e3 / KL, 2),
-              "append_unique_us": round(app_us, 2), "active_after": n_loop[0]}
+              "append_unique_us": round(app_us, 2), "topk_logprob_us": round(lp_us, 2), "active_after": n_loop[0]}
 
     # dense comparison point: full-vocabulary head + top-k over V
     dense = None

@@ -157,6 +157,17 @@ NANOSPEC_API nanospec_status nanospec_sparse_head(nanospec_state* st, const void
 NANOSPEC_API nanospec_status nanospec_topk_remap(nanospec_state* st, const float* d_logits, int32_t M, int32_t k,
                                     int32_t* d_out_ids, float* d_out_vals, void* hip_stream);
 
+/* Draft-token selection with the draft distribution renormalised over the active vocabulary (Sec. 4.2
+ * attributes the acceptance gain on context-heavy tasks to exactly this renormalisation; tree-style
+ * drafters rank their nodes by these log-probabilities): ids and order as nanospec_topk_remap, values
+ *   logprob[b][m][r] = z_r - log(sum_{j < n_b} exp(logits[b][m][j])),
+ * fp32, the sum taken after subtracting the row maximum, partial sums added in a fixed order (the
+ * result is reproducible bit for bit).  Slots beyond n_b get id -1 and -inf.
+ *   d_out_logprob : fp32 [batch][M][k], required.
+ * Errors: EINVAL, ECAPACITY (M > m_cap or k > k_cap).  Asynchronous. */
+NANOSPEC_API nanospec_status nanospec_topk_logprob_remap(nanospec_state* st, const float* d_logits, int32_t M, int32_t k,
+                                                         int32_t* d_out_ids, float* d_out_logprob, void* hip_stream);
+
 /* Dense full-vocabulary head, Eq. 1: logits[m][v] = sum_c W[v][c] * H[m][c] for all v < V.
  *   d_logits : fp32 [M_total][V].  Stateless.  Errors: EINVAL (null, sizes < 1, d % 8 != 0).
  * Asynchronous. */

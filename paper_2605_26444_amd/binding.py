@@ -22,7 +22,7 @@ MAX_BATCH = 256
 EXPORTS = [
     "nanospec_status_string", "nanospec_state_layout", "nanospec_create", "nanospec_destroy",
     "nanospec_vocab_init", "nanospec_vocab_update", "nanospec_vocab_append_unique", "nanospec_vocab_view", "nanospec_sparse_head",
-    "nanospec_topk_remap", "nanospec_dense_head", "nanospec_dense_topk_workspace", "nanospec_dense_topk",
+    "nanospec_topk_remap", "nanospec_topk_logprob_remap", "nanospec_dense_head", "nanospec_dense_topk_workspace", "nanospec_dense_topk",
     "nanospec_last_device_error",
 ]
 
@@ -63,6 +63,7 @@ def lib() -> C.CDLL:
         L.nanospec_vocab_view.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), i32p]
         L.nanospec_sparse_head.argtypes = [vp, vp, vp, i32, vp, vp]
         L.nanospec_topk_remap.argtypes = [vp, vp, i32, i32, vp, vp, vp]
+        L.nanospec_topk_logprob_remap.argtypes = [vp, vp, i32, i32, vp, vp, vp]
         L.nanospec_dense_head.argtypes = [vp, vp, i32, i32, i32, vp, vp]
         L.nanospec_dense_topk_workspace.restype = i64
         L.nanospec_dense_topk_workspace.argtypes = [i32, i32, i32]
@@ -156,6 +157,11 @@ def nanospec_sparse_head(st, d_W, d_H, M, d_logits, stream=None):
 def nanospec_topk_remap(st, d_logits, M, k, d_out_ids, d_out_vals=None, stream=None):
     _check(lib().nanospec_topk_remap(st, _ptr(d_logits), M, k, _ptr(d_out_ids), _ptr(d_out_vals), _stream(stream)),
            "nanospec_topk_remap")
+
+
+def nanospec_topk_logprob_remap(st, d_logits, M, k, d_out_ids, d_out_logprob, stream=None):
+    _check(lib().nanospec_topk_logprob_remap(st, _ptr(d_logits), M, k, _ptr(d_out_ids), _ptr(d_out_logprob),
+                                             _stream(stream)), "nanospec_topk_logprob_remap")
 
 
 def nanospec_dense_head(d_W, d_H, V, d, M_total, d_logits, stream=None):

@@ -200,7 +200,18 @@ nanospec_status nanospec_topk_remap(nanospec_state* st, const float* d_logits, i
   if (!st || !d_logits || !d_out_ids || M < 1 || k < 1) return NANOSPEC_EINVAL;
   if (M > st->m_cap || k > st->k_cap) return NANOSPEC_ECAPACITY;
   hipError_t e = launch_topk(d_logits, st->vp.cap, st->vp.ids, st->vp.cap, st->vp.n, 0, st->vp.cap, st->batch, M, k,
-                             d_out_ids, d_out_vals, st->topk_ws, st->topk_ws_bytes, static_cast<hipStream_t>(hip_stream));
+                             d_out_ids, d_out_vals, false, st->topk_ws, st->topk_ws_bytes,
+                             static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;
+}
+
+nanospec_status nanospec_topk_logprob_remap(nanospec_state* st, const float* d_logits, int32_t M, int32_t k,
+                                            int32_t* d_out_ids, float* d_out_logprob, void* hip_stream) {
+  if (!st || !d_logits || !d_out_ids || !d_out_logprob || M < 1 || k < 1) return NANOSPEC_EINVAL;
+  if (M > st->m_cap || k > st->k_cap) return NANOSPEC_ECAPACITY;
+  hipError_t e = launch_topk(d_logits, st->vp.cap, st->vp.ids, st->vp.cap, st->vp.n, 0, st->vp.cap, st->batch, M, k,
+                             d_out_ids, d_out_logprob, true, st->topk_ws, st->topk_ws_bytes,
+                             static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;
 }
 
@@ -223,7 +234,7 @@ nanospec_status nanospec_dense_topk(const float* d_logits, int32_t V, int32_t M_
   if (!d_logits || !d_out_ids || !d_workspace || V < 1 || M_total < 1 || k < 1 || k > kMaxK) return NANOSPEC_EINVAL;
   if ((int64_t)V > (int64_t)kTopkChunk * 16) return NANOSPEC_EINVAL;
   if (workspace_bytes < nanospec_dense_topk_workspace(V, M_total, k)) return NANOSPEC_ECAPACITY;
-  hipError_t e = launch_topk(d_logits, V, nullptr, 0, nullptr, V, V, 1, M_total, k, d_out_ids, d_out_vals,
+  hipError_t e = launch_topk(d_logits, V, nullptr, 0, nullptr, V, V, 1, M_total, k, d_out_ids, d_out_vals, false,
                              static_cast<char*>(d_workspace), workspace_bytes, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;
 }

@@ -66,6 +66,6 @@ hipError_t launch_head(const void* W, const void* H, const int32_t* ids, const i
 int64_t topk_workspace_bytes(int32_t cap, int32_t rows, int32_t k);
 hipError_t launch_topk(const float* logits, int64_t ld, const int32_t* ids, int64_t ids_stride, const int32_t* n_dev,
                        int32_t n_fixed, int32_t cap, int32_t batch, int32_t M, int32_t k, int32_t* out_ids,
-                       float* out_vals, char* ws, int64_t ws_bytes, hipStream_t s);
+                       float* out_vals, bool logprob, char* ws, int64_t ws_bytes, hipStream_t s);
 
 }  // namespace nanospec

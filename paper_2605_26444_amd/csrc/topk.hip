@@ -16,6 +16,12 @@
 // >= T can be winners.  They are compacted in position order into LDS (typically one or two dozen),
 // every thread ranks one candidate against all others, and rank r < k is output slot r.  If more
 // than kCandMax elements survive (heavy ties) the kernel falls back to the rounds.
+//
+// LSE variants (Sec. 4.2: the draft distribution is the softmax renormalised over the active set):
+// the same selection, with the values written as log-probabilities z - log(sum_i exp z_i), i over the
+// row's n entries.  The row maximum falls out of the first threshold round, the sum of exp(z - max)
+// is taken wavefront by wavefront and added in wavefront order (chunk order in the merge kernel), so
+// the result does not depend on timing.
 #include <limits.h>
 
 #include "common.h"
@@ -30,6 +36,7 @@ __device__ __forceinline__ float dpp_max(float x) {
 }
 
 // maximum over the 64 lanes, returned in every lane
+
 __device__ __forceinline__ float wave_max(float x) {
   x = dpp_max<0x111, 0xf>(x);   // row_shr:1
   x = dpp_max<0x112, 0xf>(x);   // row_shr:2
@@ -37,6 +44,23 @@ __device__ __forceinline__ float wave_max(float x) {
   x = dpp_max<0x118, 0xf>(x);   // row_shr:8   -> lane 15 of each row holds the row maximum
   x = dpp_max<0x142, 0xa>(x);   // row_bcast:15 into rows 1 and 3
   x = dpp_max<0x143, 0xc>(x);   // row_bcast:31 into rows 2 and 3 -> lane 63 holds the maximum
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float x) {
+  const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xf, false);
+  return x + __int_as_float(y);
+}
+
+// sum over the 64 lanes in a fixed order, returned in every lane
+__device__ __forceinline__ float wave_add(float x) {
+  x = dpp_add<0x111, 0xf>(x);
+  x = dpp_add<0x112, 0xf>(x);
+  x = dpp_add<0x114, 0xf>(x);
+  x = dpp_add<0x118, 0xf>(x);
+  x = dpp_add<0x142, 0xa>(x);
+  x = dpp_add<0x143, 0xc>(x);
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
 }
 
@@ -65,12 +89,13 @@ __device__ __forceinline__ void wave_select(float (&v)[EPT], int k, int lane, Em
 
 // One workgroup of NW wavefronts selects the k best of elements [c*CH, (c+1)*CH) of row (b, m),
 // CH = NW*64*EPT.  FINAL: write global ids / values; else (value, position) for the merge kernel.
-template <int EPT, int NW, bool FINAL>
+template <int EPT, int NW, bool FINAL, bool LSE>
 __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __restrict__ logits, int64_t ld,
                                                              const int32_t* __restrict__ ids, int64_t ids_stride,
                                                              const int32_t* __restrict__ n_dev, int n_fixed, int M, int k,
                                                              int32_t* __restrict__ out_ids, float* __restrict__ out_vals,
-                                                             float* __restrict__ cand_val, int32_t* __restrict__ cand_pos) {
+                                                             float* __restrict__ cand_val, int32_t* __restrict__ cand_pos,
+                                                             float2* __restrict__ cand_ms) {
   constexpr int E2 = (NW * kMaxK + 63) / 64;
   __shared__ float s_val[NW * kMaxK];
   __shared__ int s_pos[NW * kMaxK];
@@ -103,9 +128,12 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
 #pragma unroll
     for (int e = 0; e < EPT; ++e) v[e] = (p0 + e < n) ? src[p0 + e] : -INFINITY;
   }
+  float lse = 0.f;                                        // log sum exp of the row (LSE && FINAL)
   // ---- fast path: threshold from lane maxima, compaction, ranking
   {
     __shared__ float s_thr[NW];
+    __shared__ float s_wmax[NW];
+    __shared__ float s_sum[NW];
     __shared__ int s_cnt[NW];
     __shared__ float s_cv[kCandMax];
     __shared__ int s_cp[kCandMax];
@@ -114,17 +142,43 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
     for (int e = 1; e < EPT; ++e) ml = fmaxf(ml, v[e]);
     float x = ml, thr = -INFINITY;
     const int rounds = (k + NW - 1) / NW;                  // NW * rounds >= k lanes hold something >= T
+    float wmax = -INFINITY, wsum = 0.f;
     for (int r = 0; r < rounds; ++r) {
       thr = wave_max(x);
+      if (LSE && r == 0) {                                  // the first round's result is the wavefront's maximum;
+        wmax = thr;                                         // its exp-sum is independent work between the rounds
+        const float ref = wmax == -INFINITY ? 0.f : wmax;   // nothing valid here: every term is exp(-inf) = 0
+        float se = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) se += expf(v[e] - ref);
+        wsum = wave_add(se);
+      }
       const unsigned long long ball = __ballot(x == thr);
       const int L = ball ? __ffsll(ball) - 1 : 0;
       if (lane == L) x = -INFINITY;
     }
-    if (lane == 0) s_thr[wave] = thr;
+    if (lane == 0) {
+      s_thr[wave] = thr;
+      if (LSE) {
+        s_wmax[wave] = wmax;
+        s_sum[wave] = wsum;
+      }
+    }
     __syncthreads();
     float T = s_thr[0];
 #pragma unroll
     for (int ww = 1; ww < NW; ++ww) T = fminf(T, s_thr[ww]);
+    if (LSE) {                                              // wavefront (max, sum) pairs -> the row's, in wavefront order
+      float zmax = s_wmax[0];
+#pragma unroll
+      for (int ww = 1; ww < NW; ++ww) zmax = fmaxf(zmax, s_wmax[ww]);
+      zmax = zmax == -INFINITY ? 0.f : zmax;                // empty chunk: every factor below is exp(-inf) = 0
+      float se = 0.f;
+#pragma unroll
+      for (int ww = 0; ww < NW; ++ww) se += s_sum[ww] * expf(s_wmax[ww] - zmax);
+      if (FINAL) lse = zmax + logf(se);
+      else if (tid == 0) cand_ms[row * gridDim.x + c] = make_float2(zmax, se);
+    }
     uint32_t flags = 0;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) flags |= (uint32_t)((p0 + e < n) && (v[e] >= T)) << e;
@@ -171,7 +225,7 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
           if (FINAL) {
             o = row * k + rank;
             out_ids[o] = pos < 0 ? -1 : (ids ? ids[b * ids_stride + pos] : pos);
-            if (out_vals) out_vals[o] = val;
+            if (out_vals) out_vals[o] = (LSE && val != -INFINITY) ? val - lse : val;
           } else {
             o = (row * gridDim.x + c) * k + rank;
             cand_val[o] = val;
@@ -214,7 +268,7 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
     if (FINAL) {
       const int64_t o = row * k + lane;
       out_ids[o] = none ? -1 : (ids ? ids[b * ids_stride + pos] : pos);
-      if (out_vals) out_vals[o] = wval;
+      if (out_vals) out_vals[o] = (LSE && !none) ? wval - lse : wval;
     } else {
       const int64_t o = (row * gridDim.x + c) * k + lane;
       cand_val[o] = wval;
@@ -224,10 +278,11 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
 }
 
 // Merge the per-chunk winners of one row (nchunks*k <= 1024 candidates, in position order).
+template <bool LSE>
 __global__ __launch_bounds__(64) void topk_merge_kernel(const float* __restrict__ cand_val, const int32_t* __restrict__ cand_pos,
-                                                        int nchunks, const int32_t* __restrict__ ids, int64_t ids_stride,
-                                                        int M, int k, int32_t* __restrict__ out_ids,
-                                                        float* __restrict__ out_vals) {
+                                                        const float2* __restrict__ cand_ms, int nchunks,
+                                                        const int32_t* __restrict__ ids, int64_t ids_stride, int M, int k,
+                                                        int32_t* __restrict__ out_ids, float* __restrict__ out_vals) {
   constexpr int EPT = 16;
   const int m = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
   const int64_t row = (int64_t)b * M + m;
@@ -239,6 +294,22 @@ __global__ __launch_bounds__(64) void topk_merge_kernel(const float* __restrict_
   for (int e = 0; e < EPT; ++e) {
     const int q = lane * EPT + e;
     v[e] = (q < total) ? cv[q] : -INFINITY;
+  }
+  float lse = 0.f;
+  if (LSE) {                                              // chunk (max, sum) pairs -> one log sum exp, in chunk order
+    const float2* ms = cand_ms + row * nchunks;
+    float zmax = -INFINITY;
+    for (int q = lane; q < nchunks; q += 64) zmax = fmaxf(zmax, ms[q].y > 0.f ? ms[q].x : -INFINITY);
+    zmax = wave_max(zmax);
+    zmax = zmax == -INFINITY ? 0.f : zmax;
+    float se = 0.f;
+    for (int q0 = 0; q0 < nchunks; q0 += 64) {
+      const int q = q0 + lane;
+      float t = 0.f;
+      if (q < nchunks && ms[q].y > 0.f) t = ms[q].y * expf(ms[q].x - zmax);
+      se += wave_add(t);
+    }
+    lse = zmax + logf(se);
   }
   float wval = -INFINITY;
   int wq = 0;
@@ -253,7 +324,7 @@ __global__ __launch_bounds__(64) void topk_merge_kernel(const float* __restrict_
     const int pos = none ? -1 : cp[wq];
     const int64_t o = row * k + lane;
     out_ids[o] = none ? -1 : (ids ? ids[b * ids_stride + pos] : pos);
-    if (out_vals) out_vals[o] = wval;
+    if (out_vals) out_vals[o] = (LSE && !none) ? wval - lse : wval;
   }
 }
 
@@ -261,34 +332,46 @@ static int chunks_for(int32_t cap) { return (cap + kTopkChunk - 1) / kTopkChunk;
 
 int64_t topk_workspace_bytes(int32_t cap, int32_t rows, int32_t k) {
   if (cap <= kTopkChunk) return 0;
-  return (int64_t)rows * chunks_for(cap) * k * 8;
+  return (int64_t)rows * chunks_for(cap) * (k * 8 + 8);   // (value, position) per winner + (max, sum) per chunk
 }
 
-hipError_t launch_topk(const float* logits, int64_t ld, const int32_t* ids, int64_t ids_stride, const int32_t* n_dev,
-                       int32_t n_fixed, int32_t cap, int32_t batch, int32_t M, int32_t k, int32_t* out_ids,
-                       float* out_vals, char* ws, int64_t ws_bytes, hipStream_t s) {
+template <bool LSE>
+static hipError_t launch_topk_t(const float* logits, int64_t ld, const int32_t* ids, int64_t ids_stride, const int32_t* n_dev,
+                                int32_t n_fixed, int32_t cap, int32_t batch, int32_t M, int32_t k, int32_t* out_ids,
+                                float* out_vals, char* ws, int64_t ws_bytes, hipStream_t s) {
   const dim3 rows(1, M, batch);
   if (cap <= 4096) {
-    topk_select_kernel<16, 4, true><<<rows, 256, 0, s>>>(logits, ld, ids, ids_stride, n_dev, n_fixed, M, k, out_ids, out_vals,
-                                                       nullptr, nullptr);
+    topk_select_kernel<16, 4, true, LSE><<<rows, 256, 0, s>>>(logits, ld, ids, ids_stride, n_dev, n_fixed, M, k, out_ids,
+                                                            out_vals, nullptr, nullptr, nullptr);
     return hipGetLastError();
   }
   if (cap <= kTopkChunk) {
-    topk_select_kernel<16, 16, true><<<rows, 1024, 0, s>>>(logits, ld, ids, ids_stride, n_dev, n_fixed, M, k, out_ids,
-                                                         out_vals, nullptr, nullptr);
+    topk_select_kernel<16, 16, true, LSE><<<rows, 1024, 0, s>>>(logits, ld, ids, ids_stride, n_dev, n_fixed, M, k, out_ids,
+                                                              out_vals, nullptr, nullptr, nullptr);
     return hipGetLastError();
   }
   const int nch = chunks_for(cap);
   const int64_t need = topk_workspace_bytes(cap, batch * M, k);
   if (nch * k > 1024 || ws == nullptr || ws_bytes < need) return hipErrorInvalidValue;
+  const int64_t slots = (int64_t)batch * M * nch * k;
   float* cv = reinterpret_cast<float*>(ws);
-  int32_t* cp = reinterpret_cast<int32_t*>(ws + need / 2);
-  topk_select_kernel<16, 16, false><<<dim3(nch, M, batch), 1024, 0, s>>>(logits, ld, ids, ids_stride, n_dev, n_fixed, M, k,
-                                                                       nullptr, nullptr, cv, cp);
+  int32_t* cp = reinterpret_cast<int32_t*>(ws + slots * 4);
+  float2* ms = reinterpret_cast<float2*>(ws + slots * 8);
+  topk_select_kernel<16, 16, false, LSE><<<dim3(nch, M, batch), 1024, 0, s>>>(logits, ld, ids, ids_stride, n_dev, n_fixed, M,
+                                                                            k, nullptr, nullptr, cv, cp, ms);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  topk_merge_kernel<<<rows, 64, 0, s>>>(cv, cp, nch, ids, ids_stride, M, k, out_ids, out_vals);
+  topk_merge_kernel<LSE><<<rows, 64, 0, s>>>(cv, cp, ms, nch, ids, ids_stride, M, k, out_ids, out_vals);
   return hipGetLastError();
+}
+
+hipError_t launch_topk(const float* logits, int64_t ld, const int32_t* ids, int64_t ids_stride, const int32_t* n_dev,
+                       int32_t n_fixed, int32_t cap, int32_t batch, int32_t M, int32_t k, int32_t* out_ids,
+                       float* out_vals, bool logprob, char* ws, int64_t ws_bytes, hipStream_t s) {
+  return logprob ? launch_topk_t<true>(logits, ld, ids, ids_stride, n_dev, n_fixed, cap, batch, M, k, out_ids, out_vals, ws,
+                                       ws_bytes, s)
+                 : launch_topk_t<false>(logits, ld, ids, ids_stride, n_dev, n_fixed, cap, batch, M, k, out_ids, out_vals, ws,
+                                        ws_bytes, s);
 }
 
 }  // namespace nanospec

@@ -267,6 +267,8 @@ def test_argument_errors():
     assert L.nanospec_sparse_head(st.h, buf.data_ptr(), buf.data_ptr(), 4, buf.data_ptr(), None) == B.ECAPACITY
     assert L.nanospec_sparse_head(st.h, None, buf.data_ptr(), 1, buf.data_ptr(), None) == B.EINVAL
     assert L.nanospec_topk_remap(st.h, buf.data_ptr(), 1, 65, buf.data_ptr(), None, None) == B.ECAPACITY
+    assert L.nanospec_topk_logprob_remap(st.h, buf.data_ptr(), 1, 1, buf.data_ptr(), None, None) == B.EINVAL   # values required
+    assert L.nanospec_topk_logprob_remap(st.h, buf.data_ptr(), 4, 1, buf.data_ptr(), buf.data_ptr(), None) == B.ECAPACITY
     assert L.nanospec_dense_head(buf.data_ptr(), buf.data_ptr(), 10, 12, 1, buf.data_ptr(), None) == B.EINVAL
     assert L.nanospec_dense_topk(buf.data_ptr(), 100000, 1, 4, buf.data_ptr(), None, buf.data_ptr(), 8, None) == B.ECAPACITY
     torch.cuda.synchronize()
@@ -415,3 +417,47 @@ def test_device_side_feedback_loop():
         assert B.lib().nanospec_vocab_append_unique(st.h, None, 4, 4, None) == B.EINVAL
         assert B.lib().nanospec_vocab_append_unique(st.h, oi.data_ptr(), 4, 2, None) == B.EINVAL
         st.close()
+
+
+@pytest.mark.parametrize("window,n_ctx", [(64, 0), (64, 7), (3500, 3000), (12000, 9000), (40000, 33000)])
+def test_topk_logprob_against_oracle(window, n_ctx):
+    """Selection with log-probabilities renormalised over the active set (Sec. 4.2): ids bit-exact against
+    the oracle's selection; values within 1e-4 of the fp64 log-softmax (fp32 exp and a sum of at most 4e4
+    positive terms: relative error of the sum below 1e-5, so below 1e-5 absolute in its logarithm; the
+    final subtraction rounds at 1e-6 for |z - lse| < 16)."""
+    V, d, M, k = 50000, 8, 4, 10
+    st = B.State(V, d, 1, window, 0, M, 64)
+    rng = np.random.default_rng(window + n_ctx)
+    ctx = rng.choice(V, size=n_ctx, replace=False).astype(np.int32)
+    B.nanospec_vocab_init(st.h, dev_ids(ctx), [0, n_ctx], None, [0, 0])
+    act = st.read_active()[0]
+    n, cap = len(act), st.capacity
+    assert n == n_ctx
+    z = np.full((1, M, cap), np.nan, np.float32)
+    z[0, 0, :n] = rng.normal(size=n) * 3.0
+    z[0, 1, :n] = np.round(rng.normal(size=n) * 2.0) / 2.0         # many ties
+    z[0, 2, :n] = -7.5                                            # all equal: the general path, logp = -log n
+    z[0, 3, :n] = rng.normal(size=n) * 0.01 + 80.0                # large offset: the maximum must be subtracted
+    lg = dev(z)
+    oi = torch.empty((1, M, k), dtype=torch.int32, device="cuda")
+    ov = torch.empty((1, M, k), dtype=torch.float32, device="cuda")
+    B.nanospec_topk_logprob_remap(st.h, lg, M, k, oi, ov)
+    torch.cuda.synchronize()
+    gi, gv = oi.cpu().numpy()[0], ov.cpu().numpy()[0]
+    for m in range(M):
+        ei, elp = oracle.topk_logprob(z[0, m, :n], act, k)
+        assert np.array_equal(gi[m], ei), f"row {m}"
+        fin = np.isfinite(elp)
+        assert np.array_equal(np.isneginf(gv[m]), ~fin)
+        assert np.all(np.abs(gv[m][fin].astype(np.float64) - elp[fin]) <= 1e-4), f"row {m}"
+    if n:
+        assert abs(float(gv[2, 0]) + np.log(n)) <= 1e-4
+    # plain selection on the same logits: same ids; and a second run gives the same bits
+    oi2 = torch.empty_like(oi)
+    ov2 = torch.empty_like(ov)
+    B.nanospec_topk_remap(st.h, lg, M, k, oi2, None)
+    assert torch.equal(oi, oi2)
+    B.nanospec_topk_logprob_remap(st.h, lg, M, k, oi2, ov2)
+    torch.cuda.synchronize()
+    assert torch.equal(oi, oi2) and torch.equal(ov.view(torch.int32), ov2.view(torch.int32))
+    st.close()

@@ -124,8 +124,11 @@ NANOSPEC_API nanospec_status nanospec_vocab_update(nanospec_state* st, const int
  * ascending id order (the paper leaves the order of tuple(set) open), then Eq. 4 as in
  * nanospec_vocab_update.  The number of ids appended is known only on the device.  Entries equal to -1
  * (top-k padding) are skipped; other ids outside [0,V) are skipped and raise NANOSPEC_DEV_BAD_ID.  T is kept.
- *   d_cand_ids : device int32 [batch][cand_stride]; cand_per_seq <= m_cap * k_cap.
- * Errors: EINVAL (null, negative, stride < count), ECAPACITY.  Asynchronous; takes no host integers that
+ * The same call finishes Eq. 2 on the device: after nanospec_vocab_init with the prompt, pass the [L][K_pre]
+ * output of nanospec_dense_topk over the prefill logits (the tail of S^(0) is a de-duplicated union too).
+ *   d_cand_ids : device int32 [batch][cand_stride]; cand_per_seq is bounded by the LDS of one workgroup:
+ *                40800 - 12 * ceil(V/128) entries (28 776 at V = 128256); at least m_cap * k_cap.
+ * Errors: EINVAL (null, negative, stride < count), ECAPACITY (cand_per_seq above that bound).  Asynchronous; takes no host integers that
  * change from step to step, so one recorded HIP graph of a whole draft step can be replayed indefinitely. */
 NANOSPEC_API nanospec_status nanospec_vocab_append_unique(nanospec_state* st, const int32_t* d_cand_ids,
                                                           int32_t cand_per_seq, int64_t cand_stride, void* hip_stream);

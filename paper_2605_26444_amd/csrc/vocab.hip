@@ -204,9 +204,10 @@ __global__ __launch_bounds__(kVocabThreads) void vocab_append_unique_kernel(Voca
 
 hipError_t vocab_configure(nanospec_state* st) {
   st->vocab_lds_bytes = (2 * st->vp.nwords + 32) * 4;
-  st->unique_cap = st->m_cap * st->k_cap;
+  // candidates per call are bounded by what is left of the 160 KB of LDS after three bitmaps
+  st->unique_cap = (160 * 1024 - 512) / 4 - (3 * st->vp.nwords + 32);
+  if (st->unique_cap < st->m_cap * st->k_cap) return hipErrorInvalidValue;
   st->unique_lds_bytes = (3 * st->vp.nwords + 32 + st->unique_cap) * 4;
-  if (st->unique_lds_bytes > 160 * 1024 - 512) return hipErrorInvalidValue;
   hipError_t e = hipSuccess;
   if (st->vocab_lds_bytes > 48 * 1024)
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(vocab_apply_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -234,8 +235,9 @@ hipError_t launch_vocab_apply(const nanospec_state* st, const int32_t* d_new, co
 
 hipError_t launch_vocab_append_unique(const nanospec_state* st, const int32_t* d_cand, int per_seq, int64_t stride,
                                       hipStream_t s) {
-  vocab_append_unique_kernel<<<st->batch, kVocabThreads, st->unique_lds_bytes, s>>>(st->vp, d_cand, per_seq, stride,
-                                                                                  st->unique_cap);
+  const int ucap = per_seq < st->V ? per_seq : st->V;       // no more distinct ids than candidates or tokens
+  const int lds = (3 * st->vp.nwords + 32 + ucap) * 4;
+  vocab_append_unique_kernel<<<st->batch, kVocabThreads, lds, s>>>(st->vp, d_cand, per_seq, stride, ucap);
   return hipGetLastError();
 }
 

@@ -413,7 +413,7 @@ def test_device_side_feedback_loop():
                 assert B.nanospec_last_device_error(st.h) == B.DEV_BAD_ID
         assert B.nanospec_last_device_error(st.h) == 0
         import ctypes as C
-        assert B.lib().nanospec_vocab_append_unique(st.h, oi.data_ptr(), M * k + 1, M * k + 1, None) == B.ECAPACITY
+        assert B.lib().nanospec_vocab_append_unique(st.h, oi.data_ptr(), 41000, 41000, None) == B.ECAPACITY   # beyond the LDS bound
         assert B.lib().nanospec_vocab_append_unique(st.h, None, 4, 4, None) == B.EINVAL
         assert B.lib().nanospec_vocab_append_unique(st.h, oi.data_ptr(), 4, 2, None) == B.EINVAL
         st.close()
@@ -460,4 +460,43 @@ def test_topk_logprob_against_oracle(window, n_ctx):
     B.nanospec_topk_logprob_remap(st.h, lg, M, k, oi2, ov2)
     torch.cuda.synchronize()
     assert torch.equal(oi, oi2) and torch.equal(ov.view(torch.int32), ov2.view(torch.int32))
+    st.close()
+
+
+@pytest.mark.parametrize("window", [64, 700, 4096])
+def test_prefill_stream_initialisation_on_device(window):
+    """Eq. 2 composed on the device: S(0) = prompt, then the de-duplicated union of the top-K_pre ids of every
+    prompt position.  The prefill logits are synthetic (the target model is outside the path); the top-K_pre
+    ids come from nanospec_dense_topk over the L x V matrix and go into the stream without a host copy.
+    Windows shorter than the appended union exercise ids that enter and leave within one call."""
+    V, d, L, Kpre = 32000, 8, 300, 3
+    rng = np.random.default_rng(window)
+    zipf = synth.ZipfVocab(V, 1.1, seed=5)
+    prompt = zipf.tokens(6, 0, L).astype(np.int32)
+    Z = rng.normal(size=(L, V)).astype(np.float32)
+    hot = zipf.tokens(7, 0, 40).astype(np.int64)                    # a few tokens are likely at many positions
+    Z[:, hot] += rng.normal(size=(L, len(hot))).astype(np.float32) * 2.0 + 2.0
+    dZ = dev(Z)
+    ws_bytes = B.nanospec_dense_topk_workspace(V, L, Kpre)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    pre_ids = torch.empty((L, Kpre), dtype=torch.int32, device="cuda")
+    B.nanospec_dense_topk(dZ, V, L, Kpre, pre_ids, None, ws, ws_bytes)
+    st = B.State(V, d, 1, window, 16, 4, 8)
+    T = np.array([3, 31999, 17], np.int32)
+    B.nanospec_vocab_init(st.h, dev(prompt), [0, L], dev(T), [0, len(T)])
+    B.nanospec_vocab_append_unique(st.h, pre_ids, L * Kpre, L * Kpre)
+    torch.cuda.synchronize()
+    gi = pre_ids.cpu().numpy()
+    allids = np.arange(V, dtype=np.int32)
+    union = set()
+    for i in range(L):
+        ei, _ = oracle.topk(Z[i], allids, Kpre)
+        assert np.array_equal(gi[i], ei), i
+        union.update(int(x) for x in ei)
+    assert len(union) < L * Kpre                                    # the synthetic logits do produce repeats
+    orc = oracle.Vocab(V, window)
+    orc.init(prompt, T)
+    orc.append_unique(np.array(sorted(union), np.int32)[::-1])      # any order: the oracle takes the set
+    assert np.array_equal(st.read_active()[0], orc.active())
+    assert B.nanospec_last_device_error(st.h) == 0
     st.close()

@@ -170,6 +170,30 @@ def main():
     upd_us = train(lambda i, cs: B.nanospec_vocab_update(st.h, d_new, zero_off, None, None, cs))
     topk_us = train(lambda i, cs: B.nanospec_topk_remap(st.h, logits, M, k, out_ids, out_vals, cs))
 
+    # The paper's own system design (Sec. 3.3: rows of new active ids are copied into a pre-allocated packed
+    # buffer and the head is a dense product on that buffer) as a measured comparison point: the same active
+    # rows packed contiguously once (torch.index_select, outside the timed region), the dense kernel on the
+    # packed buffer with the same cold rotation, and the copy of one step's new rows into the buffer.
+    packed_variant = None
+    if Bn == 1 and not args.no_dense:
+        act0 = to_dev(st.read_active()[0].astype(np.int64))
+        n0 = int(act0.numel())
+        packed = [Wd[r].index_select(0, act0).contiguous() for r in range(R)]
+        pl = torch.empty((M, n0), dtype=torch.float32, device="cuda")
+        packed_us = train(lambda i, cs: B.nanospec_dense_head(packed[i % R], Hd[i % NH], n0, d, M, pl, cs))
+        newrows, slot = act0[:4].clone(), torch.arange(4, device="cuda")
+        for i in range(3):
+            packed[i % R].index_copy_(0, slot, Wd[i % R].index_select(0, newrows))
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(50):
+            packed[i % R].index_copy_(0, slot, Wd[i % R].index_select(0, newrows))
+        e1.record()
+        torch.cuda.synchronize()
+        packed_variant = {"packed_dense_head_us": round(packed_us, 2), "fused_gather_head_us": round(head_us, 2),
+                          "copy_4_new_rows_us": round(e0.elapsed_time(e1) * 1e3 / 50, 2), "rows": n0}
+        del packed
+
     # closed loop on the device (Eq. 3 for C_draft): every step feeds the previous step's top-k ids of all M
     # nodes back into the stream with nanospec_vocab_append_unique -- no host integers at all -- and the
     # selection returns log-probabilities renormalised over the active set (Sec. 4.2)
@@ -243,6 +267,7 @@ def main():
                      "bytes_per_launch": alg_bytes, "us_per_launch": round(head_us, 3)},
         "kernels_us": {"vocab_update": round(upd_us, 2), "sparse_head": round(head_us, 2), "topk_remap": round(topk_us, 2)},
         "closed_loop": closed,
+        "packed_buffer_variant": packed_variant,
         "dense": dense,
         "cpu_baseline": cpu,
         "setup_s": round(time.time() - t0, 1),

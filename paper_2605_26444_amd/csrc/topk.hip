@@ -10,10 +10,11 @@
 // them.  Rows longer than one workgroup's reach are cut into chunks whose winners a second kernel
 // merges the same way.  Values of -inf mark "nothing left" (logits are finite by contract).
 //
-// Fast path in front of the rounds: the valid runs of a row are split evenly over the wavefronts; if
-// every wavefront reports its ceil(k/NW)-th largest lane maximum, the smallest of those is a lower
-// bound T on the row's k-th largest value (at least k lanes hold something >= T), so only elements
-// >= T can be winners.  They are compacted in position order into LDS (typically one or two dozen),
+// Fast path in front of the rounds: the valid runs of a row are split evenly over as many wavefronts
+// as gives each about 32 lanes of work (nwe <= NW; measured: spreading 150 runs over 16 wavefronts
+// loosens the bound below and costs 2-10 us on wide batches); if every such wavefront reports its
+// ceil(k/nwe)-th largest lane maximum, the smallest of those is a lower bound T on the row's k-th
+// largest value (at least k lanes hold something >= T), so only elements >= T can be winners.  They are compacted in position order into LDS (typically one or two dozen),
 // every thread ranks one candidate against all others, and rank r < k is output slot r.  If more
 // than kCandMax elements survive (heavy ties) the kernel falls back to the rounds.
 //
@@ -109,7 +110,9 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
   const int cbase = c * (NW * 64 * EPT);
   const int left = n - cbase;
   const int runs = left > 0 ? (left + EPT - 1) / EPT : 0;
-  int per_wave = (runs + NW - 1) / NW;
+  int nwe = (runs + 31) / 32;                              // wavefronts that take part
+  nwe = nwe < 1 ? 1 : (nwe > NW ? NW : nwe);
+  int per_wave = (runs + nwe - 1) / nwe;
   per_wave = per_wave > 64 ? 64 : per_wave;
   const int p0 = lane < per_wave ? cbase + (wave * per_wave + lane) * EPT : INT_MAX - EPT;   // first position of this lane's run
 
@@ -141,11 +144,11 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
 #pragma unroll
     for (int e = 1; e < EPT; ++e) ml = fmaxf(ml, v[e]);
     float x = ml, thr = -INFINITY;
-    const int rounds = (k + NW - 1) / NW;                  // NW * rounds >= k lanes hold something >= T
+    const int rounds = (k + nwe - 1) / nwe;                // nwe * rounds >= k lanes hold something >= T
     float wmax = -INFINITY, wsum = 0.f;
     for (int r = 0; r < rounds; ++r) {
       thr = wave_max(x);
-      if (LSE && r == 0) {                                  // the first round's result is the wavefront's maximum;
+      if (LSE && r == 0 && wave < nwe) {                    // the first round's result is the wavefront's maximum;
         wmax = thr;                                         // its exp-sum is independent work between the rounds
         const float ref = wmax == -INFINITY ? 0.f : wmax;   // nothing valid here: every term is exp(-inf) = 0
         float se = 0.f;
@@ -167,15 +170,12 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
     __syncthreads();
     float T = s_thr[0];
 #pragma unroll
-    for (int ww = 1; ww < NW; ++ww) T = fminf(T, s_thr[ww]);
+    for (int ww = 1; ww < NW; ++ww) T = fminf(T, ww < nwe ? s_thr[ww] : INFINITY);
     if (LSE) {                                              // wavefront (max, sum) pairs -> the row's, in wavefront order
-      float zmax = s_wmax[0];
-#pragma unroll
-      for (int ww = 1; ww < NW; ++ww) zmax = fmaxf(zmax, s_wmax[ww]);
+      const float wm = lane < NW ? s_wmax[lane] : -INFINITY;   // lane ww holds wavefront ww's pair
+      float zmax = wave_max(wm);
       zmax = zmax == -INFINITY ? 0.f : zmax;                // empty chunk: every factor below is exp(-inf) = 0
-      float se = 0.f;
-#pragma unroll
-      for (int ww = 0; ww < NW; ++ww) se += s_sum[ww] * expf(s_wmax[ww] - zmax);
+      const float se = wave_add(lane < NW ? s_sum[lane] * expf(wm - zmax) : 0.f);
       if (FINAL) lse = zmax + logf(se);
       else if (tid == 0) cand_ms[row * gridDim.x + c] = make_float2(zmax, se);
     }

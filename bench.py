@@ -175,7 +175,7 @@ def main():
     # rows packed contiguously once (torch.index_select, outside the timed region), the dense kernel on the
     # packed buffer with the same cold rotation, and the copy of one step's new rows into the buffer.
     packed_variant = None
-    if Bn == 1 and not args.no_dense:
+    if Bn == 1 and M <= 16 and not args.no_dense:           # the stateless dense entry has no split-K workspace for wider trees
         act0 = to_dev(st.read_active()[0].astype(np.int64))
         n0 = int(act0.numel())
         packed = [Wd[r].index_select(0, act0).contiguous() for r in range(R)]

@@ -212,10 +212,13 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
         int pos = -1;
         float val = -INFINITY;
         int rank = t;                                       // padding slots when fewer than k exist
+        int gid = -1;
         if (t < C) {
           val = s_cv[t];
           pos = s_cp[t];
+          if (FINAL) gid = ids ? ids[b * ids_stride + pos] : pos;   // in flight while the candidate is ranked
           rank = 0;
+#pragma unroll 4
           for (int q = 0; q < C; ++q) {
             const float ov = s_cv[q];
             rank += (ov > val || (ov == val && q < t)) ? 1 : 0;   // list order is position order
@@ -224,7 +227,7 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
         if (rank < k) {
           if (FINAL) {
             o = row * k + rank;
-            out_ids[o] = pos < 0 ? -1 : (ids ? ids[b * ids_stride + pos] : pos);
+            out_ids[o] = gid;
             if (out_vals) out_vals[o] = (LSE && val != -INFINITY) ? val - lse : val;
           } else {
             o = (row * gridDim.x + c) * k + rank;

@@ -170,6 +170,22 @@ def main():
     upd_us = train(lambda i, cs: B.nanospec_vocab_update(st.h, d_new, zero_off, None, None, cs))
     topk_us = train(lambda i, cs: B.nanospec_topk_remap(st.h, logits, M, k, out_ids, out_vals, cs))
 
+    # What one launch of this size can reach on this chip: read-only kernels that move the head's bytes and
+    # compute nothing -- the same rows through the same id list, the same number of bytes contiguously, and the
+    # whole matrix as one long stream -- with the same cold rotation and the same timing as the head.
+    ceilings = None
+    if Bn == 1:
+        sink = torch.zeros(1024, dtype=torch.uint8, device="cuda")
+        nb = alg_bytes // 16 * 16
+        g_us = train(lambda i, cs: B.nanospec_calib_gather_read(st.h, Wd[i % R], sink, cs))
+        s_us = train(lambda i, cs: B.nanospec_calib_stream_read(Wd[i % R], nb, sink, cs))
+        full = V * d * 2
+        f_us = train(lambda i, cs: B.nanospec_calib_stream_read(Wd[i % R], full, sink, cs), 32)
+        ceilings = {"gather_same_rows_us": round(g_us, 2), "gather_same_rows_GBps": round(alg_bytes / g_us / 1e3, 1),
+                    "stream_same_bytes_us": round(s_us, 2), "stream_same_bytes_GBps": round(nb / s_us / 1e3, 1),
+                    "stream_whole_matrix_GBps": round(full / f_us / 1e3, 1),
+                    "head_over_gather": round(head_us / g_us, 3)}
+
     # The paper's own system design (Sec. 3.3: rows of new active ids are copied into a pre-allocated packed
     # buffer and the head is a dense product on that buffer) as a measured comparison point: the same active
     # rows packed contiguously once (torch.index_select, outside the timed region), the dense kernel on the
@@ -265,6 +281,7 @@ def main():
                      "traffic": float(args.traffic) if args.traffic else (
                          round(PMC_TRAFFIC_PER_ROW[args.config] * n_sum) if args.config in PMC_TRAFFIC_PER_ROW else None),
                      "bytes_per_launch": alg_bytes, "us_per_launch": round(head_us, 3)},
+        "ceilings": ceilings,
         "kernels_us": {"vocab_update": round(upd_us, 2), "sparse_head": round(head_us, 2), "topk_remap": round(topk_us, 2)},
         "closed_loop": closed,
         "packed_buffer_variant": packed_variant,

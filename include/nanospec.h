@@ -186,6 +186,17 @@ NANOSPEC_API nanospec_status nanospec_dense_topk(const float* d_logits, int32_t 
                                     int32_t* d_out_ids, float* d_out_vals, void* d_workspace,
                                     int64_t workspace_bytes, void* hip_stream);
 
+/* Measurement aids, not part of the method: read-only kernels that move the bytes the head moves and
+ * compute nothing, to measure what one launch of that size and access pattern can reach on the chip.
+ *   nanospec_calib_stream_read : reads d_buf[0, bytes) once, contiguously (bytes a multiple of 16).
+ *   nanospec_calib_gather_read : reads the d bf16 of every row W[ids_b[j]], j < n_b, of sequence 0 of the
+ *                                state's active list (the rows nanospec_sparse_head would gather).
+ *   d_sink : device scratch of at least 1024 bytes (written practically never).
+ * Errors: EINVAL (null, sizes < 1, bytes % 16 != 0).  Asynchronous. */
+NANOSPEC_API nanospec_status nanospec_calib_stream_read(const void* d_buf, int64_t bytes, void* d_sink, void* hip_stream);
+NANOSPEC_API nanospec_status nanospec_calib_gather_read(nanospec_state* st, const void* d_W_bf16, void* d_sink,
+                                                        void* hip_stream);
+
 /* Read and clear the sticky device error flags (NANOSPEC_DEV_* bits).  Synchronises `hip_stream`. */
 NANOSPEC_API nanospec_status nanospec_last_device_error(nanospec_state* st, int32_t* flags, void* hip_stream);
 

@@ -23,7 +23,7 @@ EXPORTS = [
     "nanospec_status_string", "nanospec_state_layout", "nanospec_create", "nanospec_destroy",
     "nanospec_vocab_init", "nanospec_vocab_update", "nanospec_vocab_append_unique", "nanospec_vocab_view", "nanospec_sparse_head",
     "nanospec_topk_remap", "nanospec_topk_logprob_remap", "nanospec_dense_head", "nanospec_dense_topk_workspace", "nanospec_dense_topk",
-    "nanospec_last_device_error",
+    "nanospec_calib_stream_read", "nanospec_calib_gather_read", "nanospec_last_device_error",
 ]
 
 
@@ -64,6 +64,8 @@ def lib() -> C.CDLL:
         L.nanospec_sparse_head.argtypes = [vp, vp, vp, i32, vp, vp]
         L.nanospec_topk_remap.argtypes = [vp, vp, i32, i32, vp, vp, vp]
         L.nanospec_topk_logprob_remap.argtypes = [vp, vp, i32, i32, vp, vp, vp]
+        L.nanospec_calib_stream_read.argtypes = [vp, i64, vp, vp]
+        L.nanospec_calib_gather_read.argtypes = [vp, vp, vp, vp]
         L.nanospec_dense_head.argtypes = [vp, vp, i32, i32, i32, vp, vp]
         L.nanospec_dense_topk_workspace.restype = i64
         L.nanospec_dense_topk_workspace.argtypes = [i32, i32, i32]
@@ -162,6 +164,14 @@ def nanospec_topk_remap(st, d_logits, M, k, d_out_ids, d_out_vals=None, stream=N
 def nanospec_topk_logprob_remap(st, d_logits, M, k, d_out_ids, d_out_logprob, stream=None):
     _check(lib().nanospec_topk_logprob_remap(st, _ptr(d_logits), M, k, _ptr(d_out_ids), _ptr(d_out_logprob),
                                              _stream(stream)), "nanospec_topk_logprob_remap")
+
+
+def nanospec_calib_stream_read(d_buf, nbytes, d_sink, stream=None):
+    _check(lib().nanospec_calib_stream_read(_ptr(d_buf), nbytes, _ptr(d_sink), _stream(stream)), "nanospec_calib_stream_read")
+
+
+def nanospec_calib_gather_read(st, d_W, d_sink, stream=None):
+    _check(lib().nanospec_calib_gather_read(st, _ptr(d_W), _ptr(d_sink), _stream(stream)), "nanospec_calib_gather_read")
 
 
 def nanospec_dense_head(d_W, d_H, V, d, M_total, d_logits, stream=None):

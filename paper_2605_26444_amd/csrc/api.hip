@@ -239,6 +239,20 @@ nanospec_status nanospec_dense_topk(const float* d_logits, int32_t V, int32_t M_
   return e == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;
 }
 
+nanospec_status nanospec_calib_stream_read(const void* d_buf, int64_t bytes, void* d_sink, void* hip_stream) {
+  if (!d_buf || !d_sink || bytes < 16 || bytes % 16 != 0) return NANOSPEC_EINVAL;
+  return launch_calib_stream(d_buf, bytes, d_sink, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? NANOSPEC_OK
+                                                                                                        : NANOSPEC_EHIP;
+}
+
+nanospec_status nanospec_calib_gather_read(nanospec_state* st, const void* d_W_bf16, void* d_sink, void* hip_stream) {
+  if (!st || !d_W_bf16 || !d_sink) return NANOSPEC_EINVAL;
+  return launch_calib_gather(d_W_bf16, st->V, st->d, st->vp.ids, st->vp.n, st->vp.cap, d_sink,
+                             static_cast<hipStream_t>(hip_stream)) == hipSuccess
+             ? NANOSPEC_OK
+             : NANOSPEC_EHIP;
+}
+
 nanospec_status nanospec_last_device_error(nanospec_state* st, int32_t* flags, void* hip_stream) {
   if (!st || !flags) return NANOSPEC_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);

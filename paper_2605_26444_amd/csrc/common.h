@@ -68,4 +68,9 @@ hipError_t launch_topk(const float* logits, int64_t ld, const int32_t* ids, int6
                        int32_t n_fixed, int32_t cap, int32_t batch, int32_t M, int32_t k, int32_t* out_ids,
                        float* out_vals, bool logprob, char* ws, int64_t ws_bytes, hipStream_t s);
 
+// calib.hip
+hipError_t launch_calib_stream(const void* buf, int64_t bytes, void* sink, hipStream_t s);
+hipError_t launch_calib_gather(const void* W, int32_t V, int32_t d, const int32_t* ids, const int32_t* n_dev, int32_t cap,
+                               void* sink, hipStream_t s);
+
 }  // namespace nanospec

@@ -270,6 +270,8 @@ def test_argument_errors():
     assert L.nanospec_topk_logprob_remap(st.h, buf.data_ptr(), 1, 1, buf.data_ptr(), None, None) == B.EINVAL   # values required
     assert L.nanospec_topk_logprob_remap(st.h, buf.data_ptr(), 4, 1, buf.data_ptr(), buf.data_ptr(), None) == B.ECAPACITY
     assert L.nanospec_dense_head(buf.data_ptr(), buf.data_ptr(), 10, 12, 1, buf.data_ptr(), None) == B.EINVAL
+    assert L.nanospec_calib_stream_read(buf.data_ptr(), 24, buf.data_ptr(), None) == B.EINVAL          # not a multiple of 16
+    assert L.nanospec_calib_gather_read(st.h, None, buf.data_ptr(), None) == B.EINVAL
     assert L.nanospec_dense_topk(buf.data_ptr(), 100000, 1, 4, buf.data_ptr(), None, buf.data_ptr(), 8, None) == B.ECAPACITY
     torch.cuda.synchronize()
     assert np.array_equal(st.read_active()[0], np.zeros(0, np.int32))               # nothing was enqueued
@@ -498,5 +500,25 @@ def test_prefill_stream_initialisation_on_device(window):
     orc.init(prompt, T)
     orc.append_unique(np.array(sorted(union), np.int32)[::-1])      # any order: the oracle takes the set
     assert np.array_equal(st.read_active()[0], orc.active())
+    assert B.nanospec_last_device_error(st.h) == 0
+    st.close()
+
+
+def test_calibration_reads_run_and_touch_nothing():
+    """the measurement aids only read: they return OK, leave the state and their inputs unchanged."""
+    V, d = 2000, 512
+    W = synth.normal_bf16(5, 0, (V, d), 0.02, threads=1)
+    dW = dev_bf16(W)
+    st = B.State(V, d, 1, 300, 0, 1, 1)
+    ctx = np.arange(0, 1800, 7, dtype=np.int32)
+    B.nanospec_vocab_init(st.h, dev(ctx), [0, len(ctx)], None, [0, 0])
+    before = st.read_active()[0].copy()
+    sink = torch.zeros(1024, dtype=torch.uint8, device="cuda")
+    B.nanospec_calib_gather_read(st.h, dW, sink)
+    B.nanospec_calib_stream_read(dW, V * d * 2, sink)
+    B.nanospec_calib_stream_read(dW, 16, sink)
+    torch.cuda.synchronize()
+    assert np.array_equal(st.read_active()[0], before)
+    assert np.array_equal(dW.view(torch.int16).cpu().numpy().view(np.uint16), W)
     assert B.nanospec_last_device_error(st.h) == 0
     st.close()

@@ -67,10 +67,9 @@ __global__ __launch_bounds__(256) void head_generic_kernel(const uint16_t* __res
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// Matrix-core kernel for few hidden rows (M <= 16) and MANY rows (dense head, tens of thousands of
-// active rows): same operand layout as head_quad_kernel below, but every wavefront fetches its own
-// hidden-row operands and nothing goes through LDS except the final K-slice sum.  With thousands of
-// workgroups in flight the hidden rows stay in L1/L2 and the barrier-free form is the faster one.
+// Matrix-core kernel for few hidden rows (M <= 16) when d needs several K-iterations: same operand
+// layout as head_quad_kernel below, but every wavefront fetches its own hidden-row operands and
+// nothing goes through LDS except the final K-slice sum, so the K loop carries no barrier.
 // The 16 rows of the A tile of v_mfma_f32_16x16x32_bf16 are 4 gathered rows x 4 column parts, the 16
 // columns of the B tile are 4 hidden rows x the same 4 column parts; only the diagonal (part == part)
 // 4x4 blocks of the product are kept and summed.  With operand row i = 4*row + part and the part as
@@ -86,12 +85,15 @@ template <int RT, int MT, int KS, int NW>
 __global__ __launch_bounds__(64 * NW) void head_quad_private_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
                                                         const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
                                                         int n_fixed, int V, int M, int d, int64_t ld, int64_t ids_stride,
-                                                        float* __restrict__ logits) {
+                                                        float* __restrict__ logits, int seq_first) {
   constexpr int ROWS = 4 * RT;
   __shared__ float red[NW][RT * MT * 16];
-  const int b = blockIdx.z;
+  // Several sequences: the grid is (sequence, tile) with the sequence fastest, so the workgroups in
+  // flight at one time work on the same stretch of the (ascending) id lists of all sequences and the
+  // rows the sequences share are fetched from HBM once and then found in L2 / Infinity Cache.
+  const int b = seq_first ? blockIdx.x : blockIdx.z;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int j0 = blockIdx.x * ROWS;
+  const int j0 = (seq_first ? blockIdx.y : blockIdx.x) * ROWS;
   const int orow = (lane & 15) >> 2, part = lane & 3, q = lane >> 4;   // operand row / column part / k group
   const int coff = w * (128 * KS) + q * 32 + part * 8;                  // + kb + t*128
   const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
@@ -185,8 +187,11 @@ template <int RT, int MT, int KS, int NW>
 static hipError_t run_quad_private(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
                            int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride,
                            float* logits, hipStream_t s) {
-  dim3 grid((cap_rows + 4 * RT - 1) / (4 * RT), 1, batch);
-  head_quad_private_kernel<RT, MT, KS, NW><<<grid, 64 * NW, 0, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
+  const int tiles = (cap_rows + 4 * RT - 1) / (4 * RT);
+  const int seq_first = batch > 1 && tiles <= 65535;
+  const dim3 grid = seq_first ? dim3(batch, tiles, 1) : dim3(tiles, 1, batch);
+  head_quad_private_kernel<RT, MT, KS, NW><<<grid, 64 * NW, 0, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits,
+                                                                    seq_first);
   return hipGetLastError();
 }
 
@@ -213,18 +218,19 @@ template <int NRG, int RT, int MT, int KS, bool ONEK>
 __global__ __launch_bounds__(256 * NRG) void head_quad_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
                                                               const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
                                                               int n_fixed, int V, int M, int d, int64_t ld, int64_t ids_stride,
-                                                              float* __restrict__ logits) {
+                                                              float* __restrict__ logits, int seq_first) {
   constexpr int HI = MT * KS;                      // load instructions per hidden-row K-quarter slice
   constexpr int HPW = (HI + NRG - 1) / NRG;        // of which each sharing wavefront fetches this many
   constexpr int RPG = 4 * RT;                      // rows per row group
   constexpr int NOUT = RT * MT * 16;               // outputs per row group
   static_assert(HI <= 16, "LDS budget");
   extern __shared__ __attribute__((aligned(16))) char hs[];   // 4*HI KB of hidden-row operands, then the K-quarter sums
-  const int b = blockIdx.z;
+  const int b = seq_first ? blockIdx.x : blockIdx.z;      // several sequences: sequence fastest (see head_quad_private_kernel)
+  const int tile = seq_first ? blockIdx.y : blockIdx.x;
   const int lane = threadIdx.x & 63;
   const int w = threadIdx.x >> 6;
   const int kq = w & 3, rg = w >> 2;
-  const int j0 = (blockIdx.x * NRG + rg) * RPG;
+  const int j0 = (tile * NRG + rg) * RPG;
   const int orow = (lane & 15) >> 2, part = lane & 3, q = lane >> 4;   // operand row / column part / k group
   const int coff = kq * (128 * KS) + q * 32 + part * 8;                // + kb + t*128
   const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
@@ -313,7 +319,7 @@ __global__ __launch_bounds__(256 * NRG) void head_quad_kernel(const uint16_t* __
   for (int o = threadIdx.x; o < NRG * NOUT; o += 256 * NRG) {
     const int g = o / NOUT, oo = o % NOUT;
     const int rt = oo / (MT * 16), mt = (oo / 16) % MT, r = (oo % 16) / 4, mm = oo % 4;
-    const int j = (blockIdx.x * NRG + g) * RPG + rt * 4 + r, m = mt * 4 + mm;
+    const int j = (tile * NRG + g) * RPG + rt * 4 + r, m = mt * 4 + mm;
     if (j >= n || m >= M) continue;
     const float* rr = red + (g * 4) * NOUT + oo;
     const float s = ((rr[0] + rr[NOUT]) + rr[2 * NOUT]) + rr[3 * NOUT];
@@ -337,25 +343,35 @@ static hipError_t run_quad(const uint16_t* W, const uint16_t* H, const int32_t* 
     if (e != hipSuccess) return e;
     configured = true;
   }
-  dim3 grid((cap_rows + ROWS - 1) / ROWS, 1, batch);
+  const int tiles = (cap_rows + ROWS - 1) / ROWS;
+  const int seq_first = batch > 1 && tiles <= 65535;
+  const dim3 grid = seq_first ? dim3(batch, tiles, 1) : dim3(tiles, 1, batch);
   if (d <= 512 * KS)
-    head_quad_kernel<NRG, RT, MT, KS, true><<<grid, 256 * NRG, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
+    head_quad_kernel<NRG, RT, MT, KS, true><<<grid, 256 * NRG, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits, seq_first);
   else
-    head_quad_kernel<NRG, RT, MT, KS, false><<<grid, 256 * NRG, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
+    head_quad_kernel<NRG, RT, MT, KS, false><<<grid, 256 * NRG, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits, seq_first);
   return hipGetLastError();
 }
 
-// Rows per workgroup follow the row capacity: sharing hidden rows among more row groups pays as
-// long as the launch still has about one workgroup per compute unit.
+// Which kernel (all measured on MI355X):
+//  * d fits one K-iteration (d <= 512*KS): the shared-hidden-row kernel.  Rows per workgroup follow the
+//    row capacity so that small vocabularies still spread over the chip (16 / 8 / 4 rows); with tens
+//    of thousands of rows it still wins (dense 128k head, M = 8: 174 us against 188 us barrier-free and
+//    184 us for the vendor GEMM library), and for several sequences 2 row groups of 8 rows do best
+//    (64 sequences of 2.3k rows: 189 us against 223 us barrier-free).
+//  * d needs a K loop: the barrier-free kernel (with a loop the shared form pays two barriers per
+//    iteration: 264 us against 118 us at 32k rows of d = 8192, 11.0 against 9.6 us at 1.3k rows).
 template <int MT, int KS>
 static hipError_t run_quad_auto(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
                                 int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld,
                                 int64_t ids_stride, float* logits, hipStream_t s) {
   const int64_t rows = (int64_t)cap_rows * batch;
-  if (rows >= 8192) {   // thousands of workgroups: the barrier-free kernel wins (measured at 32k rows and dense)
-    if (MT <= 2) return run_quad_private<2, MT, 8, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
-    return run_quad_private<4, MT, 4, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+  if (d > 512 * KS) {
+    if (rows < 8 * 180) return run_quad_private<1, MT, KS, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+    if (MT <= 2 || rows < 8192) return run_quad_private<2, MT, KS, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+    return run_quad_private<4, MT, KS, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
   }
+  if (batch > 1 && rows >= 8192) return run_quad<2, 2, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
   if (rows >= 16 * 180) return run_quad<4, 1, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
   if (rows >= 8 * 180) return run_quad<2, 1, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
   return run_quad<1, 1, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);

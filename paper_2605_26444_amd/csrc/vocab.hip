@@ -73,7 +73,8 @@ __device__ __forceinline__ int compact_bitmap(WordFn word, int nwords, int32_t* 
 
 // One stream update of sequence b (Eq. 3 then Eq. 4): append src[0..a), evict what leaves the window,
 // optionally replace T, rebuild the ascending active list.  wb/tb are the LDS copies of the bitmaps
-// (already loaded, any barrier needed to see them is the caller's), sc 16 ints of LDS scratch.
+// (their stores have been issued by this workgroup; the body's first barrier completes them before
+// any bit is changed), sc 16 ints of LDS scratch.
 __device__ __forceinline__ void vocab_apply_body(const VocabPtrs& p, int b, const int32_t* src, int a,
                                                  const int32_t* ts, int nt, int replace_T, uint32_t* wb, uint32_t* tb,
                                                  int* sc, int bad) {
@@ -97,7 +98,21 @@ __device__ __forceinline__ void vocab_apply_body(const VocabPtrs& p, int b, cons
   // without waiting for the result: they are inside the window afterwards whatever the order of the
   // two atomics was, so their bit is simply set -- after the barrier, so that a clear of the same id
   // by the eviction pass cannot come last.
-  for (int i = tid; i < n_evict; i += kVocabThreads) {
+  // The LDS bitmaps were filled by other threads just before this call: the first pass keeps its result
+  // in a register until a barrier has made those copies complete; later passes (appends longer than
+  // the workgroup) clear directly.
+  {
+    int e0 = -1;
+    if (tid < n_evict) {
+      int slot = oldest + tid;
+      if (slot >= W) slot -= W;
+      const int e = ring[slot];
+      if (e >= 0 && atomicSub(&cnt[e], 1u) == 1u) e0 = e;
+    }
+    __syncthreads();
+    if (e0 >= 0) atomicAnd(&wb[e0 >> 5], ~(1u << (e0 & 31)));
+  }
+  for (int i = tid + kVocabThreads; i < n_evict; i += kVocabThreads) {
     int slot = oldest + i;
     if (slot >= W) slot -= W;
     const int e = ring[slot];

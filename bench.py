@@ -30,10 +30,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
-# HBM bytes per sparse-head launch from the rocprofv3 --pmc runs summarised in
-# profiles/sparse_head_c2_pmc.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a copy kernel of
-# known size), as bytes per active row so that it follows the realised |active|.
-PMC_TRAFFIC_PER_ROW = {"c2": 25397248 / 3013}
+# Bytes per sparse-head launch that leave L2 towards HBM, from the rocprofv3 --pmc runs summarised in
+# profiles/sparse_head_c2_pmc.md and profiles/head_hbm_traffic_c3_c4_c5_pmc.md (FETCH_SIZE x 2.0 +
+# WRITE_SIZE x 1.0, factors from copy / stream kernels of known size), as bytes per active row so that it
+# follows the realised |active|.  c3: the split-K kernel without its reduce kernel; c5: measured at 32k rows.
+PMC_TRAFFIC_PER_ROW = {"c2": 25397248 / 3013, "c3": 30704947 / 2998, "c4": 767755571 / 144911,
+                       "c5@32000": 535571251 / 32007}
 
 
 def main():
@@ -265,6 +267,7 @@ def main():
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(cfg, seqs, W_host, synth)
 
+    pmc_key = f"c5@{args.target}" if args.config == "c5" else args.config
     out = {
         "metric": "sparse-head draft steps/s + gathered HBM GB/s (V=128256,d=4096,|active|~3k)" if args.config == "c2"
                   else f"sparse-head draft steps/s + gathered HBM GB/s ({args.config})",
@@ -279,7 +282,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "nanospec_sparse_head", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": float(args.traffic) if args.traffic else (
-                         round(PMC_TRAFFIC_PER_ROW[args.config] * n_sum) if args.config in PMC_TRAFFIC_PER_ROW else None),
+                         round(PMC_TRAFFIC_PER_ROW[pmc_key] * n_sum) if pmc_key in PMC_TRAFFIC_PER_ROW else None),
                      "bytes_per_launch": alg_bytes, "us_per_launch": round(head_us, 3)},
         "ceilings": ceilings,
         "kernels_us": {"vocab_update": round(upd_us, 2), "sparse_head": round(head_us, 2), "topk_remap": round(topk_us, 2)},

@@ -223,7 +223,7 @@ __global__ __launch_bounds__(256 * NRG) void head_quad_kernel(const uint16_t* __
   constexpr int HPW = (HI + NRG - 1) / NRG;        // of which each sharing wavefront fetches this many
   constexpr int RPG = 4 * RT;                      // rows per row group
   constexpr int NOUT = RT * MT * 16;               // outputs per row group
-  static_assert(HI <= 16, "LDS budget");
+  static_assert(HI <= 32, "LDS budget: 4*HI KB of hidden-row operands");
   extern __shared__ __attribute__((aligned(16))) char hs[];   // 4*HI KB of hidden-row operands, then the K-quarter sums
   const int b = seq_first ? blockIdx.x : blockIdx.z;      // several sequences: sequence fastest (see head_quad_private_kernel)
   const int tile = seq_first ? blockIdx.y : blockIdx.x;
@@ -539,8 +539,16 @@ static hipError_t launch_head_64(const uint16_t* W, const uint16_t* H, const int
                                  hipStream_t s) {
   if (M <= 4) return run_quad_auto<1, 8>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
   if (M <= 8) return run_quad_auto<2, 8>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
-  if (M <= 12) return run_quad_auto<3, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
-  if (M <= 16) return run_quad_auto<4, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+  // 9..16 hidden rows: 8 loads per row and wavefront when that makes d a single K-iteration (up to 128 KB of
+  // LDS for the hidden-row operands), else 4
+  if (M <= 12) {
+    if (d > 2048 && d <= 4096) return run_quad_auto<3, 8>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+    return run_quad_auto<3, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+  }
+  if (M <= 16) {
+    if (d > 2048 && d <= 4096) return run_quad_auto<4, 8>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+    return run_quad_auto<4, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+  }
   // wide trees: split K across workgroups while the rows alone cannot fill the chip
   const int S = (d + 511) / 512;
   const int64_t need = (int64_t)S * batch * M * cap_rows * 4;

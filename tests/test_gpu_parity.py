@@ -333,6 +333,7 @@ def test_step_recorded_in_hip_graph_replays_correctly():
 @pytest.mark.parametrize("d,M,n_ctx,batch", [
     (520, 1, 37, 1), (520, 3, 300, 2), (1032, 5, 1500, 1), (3592, 8, 3001, 1), (4096, 9, 777, 1), (1032, 13, 2900, 3),
     (520, 16, 9000, 1), (1032, 17, 1000, 1), (3592, 33, 1234, 1), (1032, 64, 17000, 1), (520, 70, 500, 1), (520, 70, 200, 2),
+    (4096, 16, 3000, 1), (3592, 12, 1500, 1), (8200, 16, 2000, 1), (8200, 8, 9000, 1), (1032, 8, 3100, 3), (4104, 6, 200, 1),
 ])
 def test_head_shapes_against_oracle(d, M, n_ctx, batch):
     """every head kernel and its ragged tails: row counts that are not multiples of the tile, hidden sizes that

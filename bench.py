@@ -14,7 +14,11 @@ target model stream gigabytes between two head calls, so the benchmark rotates t
 that have been evicted, and `roofline.achieved` is an HBM number.  `--replicas 1` gives the warm
 figure.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric / value / unit and the run parameters, `roofline` (the sparse-head kernel's
+gathered bytes per launch over its event-timed launch time, against the 8 TB/s peak, with the counter-measured
+traffic), `ceilings` (read-only kernels over the same bytes), `kernels_us`, `closed_loop` (device-side feedback
+of the selected ids), `packed_buffer_variant`, `dense` (full-vocabulary head + top-k) and `cpu_baseline` (the
+CPU oracle timed on the host cores).
 """
 from __future__ import annotations
 
@@ -30,8 +34,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
-# Bytes per sparse-head launch that leave L2 towards HBM, from the rocprofv3 --pmc runs summarised in
-# profiles/sparse_head_c2_pmc.md and profiles/head_hbm_traffic_c3_c4_c5_pmc.md (FETCH_SIZE x 2.0 +
+# Bytes per sparse-head launch that leave L2 towards HBM, from the rocprofv3 --pmc runs summarised under
+# profiles/ (FETCH_SIZE x 2.0 +
 # WRITE_SIZE x 1.0, factors from copy / stream kernels of known size), as bytes per active row so that it
 # follows the realised |active|.  c3: the split-K kernel without its reduce kernel; c5: measured at 32k rows.
 PMC_TRAFFIC_PER_ROW = {"c2": 25397248 / 3013, "c3": 30704947 / 2998, "c4": 767755571 / 144911,
@@ -53,8 +57,8 @@ def main():
     ap.add_argument("--traffic", default=None, help="HBM bytes per head launch from rocprofv3 --pmc runs (or omit)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build is single-GPU; run with --gpus 1 (the path has no collectives, "
-              "see DESIGN.md for how it would shard)", file=sys.stderr)
+        print("bench.py: this build is single-GPU; run with --gpus 1 (the path has no collectives; "
+              "sequences shard by sequence, one sequence by vocabulary range with one exchange of M x k pairs)", file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -43,6 +43,16 @@ def _lib(omp: bool = False) -> C.CDLL:
         L.oracle_vocab_init.argtypes = [C.c_void_p, i32p, C.c_int64, i32p, C.c_int64]
         L.oracle_vocab_update.argtypes = [C.c_void_p, i32p, C.c_int64, C.c_int32, i32p, C.c_int64]
         L.oracle_vocab_append_unique.argtypes = [C.c_void_p, i32p, C.c_int64]
+        L.oracle_fifo_new.restype = C.c_void_p
+        L.oracle_fifo_new.argtypes = [C.c_int32, C.c_int64]
+        L.oracle_fifo_free.argtypes = [C.c_void_p]
+        L.oracle_fifo_init.argtypes = [C.c_void_p, i32p, C.c_int64, i32p, C.c_int64]
+        L.oracle_fifo_update.argtypes = [C.c_void_p, i32p, C.c_int64, C.c_int32, i32p, C.c_int64]
+        L.oracle_fifo_append_unique.argtypes = [C.c_void_p, i32p, C.c_int64]
+        L.oracle_fifo_size.restype = C.c_int64
+        L.oracle_fifo_size.argtypes = [C.c_void_p]
+        L.oracle_fifo_active.restype = C.c_int64
+        L.oracle_fifo_active.argtypes = [C.c_void_p, i32p, C.c_int64]
         L.oracle_vocab_stream_len.restype = C.c_int64
         L.oracle_vocab_stream_len.argtypes = [C.c_void_p]
         L.oracle_vocab_active.restype = C.c_int64
@@ -97,6 +107,45 @@ class Vocab:
         n = self._L.oracle_vocab_active(self._h, None, 0)
         out = np.empty(n, dtype=np.int32)
         self._L.oracle_vocab_active(self._h, _p(out, C.c_int32), n)
+        return out
+
+
+class FifoVocab:
+    """Second reading of the vocabulary (Sec. 3.3 and the appendix on vocabulary evolution): a first-in first-out
+    queue of at most ``window`` distinct ids, plus the candidate set T.  One call pushes, in order of first
+    occurrence, the ids that are valid, not yet members when the call starts and not repeated inside the call."""
+
+    def __init__(self, V: int, window: int):
+        self._L = _lib()
+        self._h = self._L.oracle_fifo_new(V, window)
+        self.V, self.window = V, window
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            self._L.oracle_fifo_free(self._h)
+            self._h = None
+
+    def init(self, ctx, topk=()):
+        ctx, topk = _i32(ctx), _i32(topk)
+        self._L.oracle_fifo_init(self._h, _p(ctx, C.c_int32), len(ctx), _p(topk, C.c_int32), len(topk))
+
+    def update(self, new_ids, topk=None):
+        new_ids = _i32(new_ids)
+        t = _i32(topk) if topk is not None else np.zeros(0, np.int32)
+        self._L.oracle_fifo_update(self._h, _p(new_ids, C.c_int32), len(new_ids), int(topk is not None),
+                                   _p(t, C.c_int32), len(t))
+
+    def append_unique(self, cand):
+        cand = _i32(np.asarray(cand).ravel())
+        self._L.oracle_fifo_append_unique(self._h, _p(cand, C.c_int32), len(cand))
+
+    def size(self) -> int:
+        return int(self._L.oracle_fifo_size(self._h))
+
+    def active(self) -> np.ndarray:
+        n = self._L.oracle_fifo_active(self._h, None, 0)
+        out = np.empty(n, dtype=np.int32)
+        self._L.oracle_fifo_active(self._h, _p(out, C.c_int32), n)
         return out
 
 

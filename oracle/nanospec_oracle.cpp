@@ -8,6 +8,8 @@
 //       the candidate stream S is every id ever appended, in order; the active index set is
 //       I = Unique(Suffix(S, W_max)) united with a caller-supplied candidate set T.  It is
 //       recomputed from scratch from S and T each time it is asked for: std::vector + std::set.
+//   * Vocabulary, second reading (Sec. 3.3 and the appendix on vocabulary evolution): a first-in
+//       first-out queue of at most W_max distinct ids; ids already in the vocabulary are not pushed again.
 //   * Sparse head (Sec. 3.1, Eq. 1 restricted to the rows I_t):  z'[m][j] = sum_c W[I_j][c]*H[m][c],
 //       scalar accumulation in index order, once in fp32 (the precision the method computes in:
 //       bf16 operands, fp32 accumulate) and once in fp64 (to bound the rounding error).
@@ -25,6 +27,7 @@
 // inputs, closed forms, invariants, independent float64 library matmul, hand-worked cases).
 #include <algorithm>
 #include <cmath>
+#include <deque>
 #include <cstdint>
 #include <cstring>
 #include <limits>
@@ -43,6 +46,38 @@ struct Vocab {
   std::vector<int32_t> S;   // candidate stream, oldest first
   std::set<int32_t> T;      // extra candidate set
 };
+
+// Second reading of the vocabulary (Sec. 3.3, GPU-resident state management: only candidates that are new
+// to the vocabulary are pushed; App. on vocabulary evolution: the vocabulary grows monotonically up to
+// the capacity W_max and is evicted first-in first-out): a queue of at most W_max *distinct* ids.
+struct FifoVocab {
+  int32_t V;
+  int64_t window;
+  std::deque<int32_t> Q;    // members in the order they were pushed, oldest first
+  std::set<int32_t> T;
+};
+
+// One call = one batch: the ids that are valid, not members when the call starts and not seen earlier
+// in the call, in the order of their first occurrence; of those at most the last W_max are pushed, after
+// as many of the oldest members as needed have been dropped.
+void fifo_push_batch(FifoVocab* v, const int32_t* ids, int64_t n) {
+  std::set<int32_t> members(v->Q.begin(), v->Q.end());
+  std::set<int32_t> seen;
+  std::vector<int32_t> F;
+  for (int64_t i = 0; i < n; ++i) {
+    const int32_t a = ids[i];
+    if (a < 0 || a >= v->V) continue;
+    if (members.count(a) || seen.count(a)) continue;
+    seen.insert(a);
+    F.push_back(a);
+  }
+  const int64_t W = v->window;
+  const int64_t nF = static_cast<int64_t>(F.size());
+  const int64_t first = nF > W ? nF - W : 0;
+  int64_t evict = static_cast<int64_t>(v->Q.size()) + (nF - first) - W;
+  for (; evict > 0; --evict) v->Q.pop_front();
+  for (int64_t i = first; i < nF; ++i) v->Q.push_back(F[i]);
+}
 
 inline float bf16_to_float(uint16_t b) {
   uint32_t u = static_cast<uint32_t>(b) << 16;
@@ -83,7 +118,7 @@ void oracle_vocab_update(void* h, const int32_t* new_ids, int64_t n_new, int32_t
   }
 }
 
-// Eq. 3 for a candidate *set* (C_draft: all unique token indices of the draft tree): the distinct
+// Eq. 3 for a candidate *set* (C_draft: every distinct token id of the draft tree): the distinct
 // valid ids are appended in ascending order (the paper leaves the order of tuple(set) open); -1 entries
 // are padding.
 void oracle_vocab_append_unique(void* h, const int32_t* cand, int64_t n_cand) {
@@ -92,6 +127,59 @@ void oracle_vocab_append_unique(void* h, const int32_t* cand, int64_t n_cand) {
   for (int64_t i = 0; i < n_cand; ++i)
     if (cand[i] >= 0 && cand[i] < v->V) C.insert(cand[i]);
   v->S.insert(v->S.end(), C.begin(), C.end());
+}
+
+void* oracle_fifo_new(int32_t V, int64_t window) {
+  FifoVocab* v = new FifoVocab;
+  v->V = V;
+  v->window = window;
+  return v;
+}
+
+void oracle_fifo_free(void* h) { delete static_cast<FifoVocab*>(h); }
+
+void oracle_fifo_init(void* h, const int32_t* ctx, int64_t n_ctx, const int32_t* topk, int64_t n_topk) {
+  FifoVocab* v = static_cast<FifoVocab*>(h);
+  v->Q.clear();
+  v->T.clear();
+  v->T.insert(topk, topk + n_topk);
+  fifo_push_batch(v, ctx, n_ctx);
+}
+
+void oracle_fifo_update(void* h, const int32_t* new_ids, int64_t n_new, int32_t replace_T, const int32_t* topk,
+                        int64_t n_topk) {
+  FifoVocab* v = static_cast<FifoVocab*>(h);
+  fifo_push_batch(v, new_ids, n_new);
+  if (replace_T) {
+    v->T.clear();
+    v->T.insert(topk, topk + n_topk);
+  }
+}
+
+// a candidate set: its distinct valid ids in ascending order, then one batch
+void oracle_fifo_append_unique(void* h, const int32_t* cand, int64_t n_cand) {
+  FifoVocab* v = static_cast<FifoVocab*>(h);
+  std::set<int32_t> C;
+  for (int64_t i = 0; i < n_cand; ++i)
+    if (cand[i] >= 0 && cand[i] < v->V) C.insert(cand[i]);
+  std::vector<int32_t> sorted(C.begin(), C.end());
+  fifo_push_batch(v, sorted.data(), static_cast<int64_t>(sorted.size()));
+}
+
+int64_t oracle_fifo_size(void* h) { return static_cast<int64_t>(static_cast<FifoVocab*>(h)->Q.size()); }
+
+// members U T, ascending.  Returns the count; writes at most cap ids.
+int64_t oracle_fifo_active(void* h, int32_t* out, int64_t cap) {
+  FifoVocab* v = static_cast<FifoVocab*>(h);
+  std::set<int32_t> I(v->Q.begin(), v->Q.end());
+  for (int32_t t : v->T) I.insert(t);
+  int64_t n = 0;
+  for (int32_t id : I) {
+    if (id < 0 || id >= v->V) continue;
+    if (n < cap) out[n] = id;
+    ++n;
+  }
+  return n;
 }
 
 int64_t oracle_vocab_stream_len(void* h) { return static_cast<int64_t>(static_cast<Vocab*>(h)->S.size()); }

@@ -173,3 +173,104 @@ def test_append_unique_is_a_sorted_set_append():
     v.append_unique([])
     v.append_unique([-1, -1])
     assert v.stream_len() == 5
+
+
+# ---- second reading: first-in first-out queue of distinct ids (Sec. 3.3 and the appendix on vocabulary evolution)
+
+def _fifo_cases():
+    for line in open(os.path.join(GOLD, "fifo_worked_examples.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        W, calls, T, exp = [x.strip() for x in line.split("|")]
+        calls = [[] if c.strip() == "-" else [int(x) for x in c.split()] for c in calls.split(";")]
+        T = [] if T == "-" else [int(x) for x in T.split()]
+        yield int(W), calls, T, [int(x) for x in exp.split()]
+
+
+def test_fifo_worked_examples():
+    n = 0
+    for W, calls, T, exp in _fifo_cases():
+        v = oracle.FifoVocab(100, W)
+        v.init(calls[0], T)
+        for c in calls[1:]:
+            v.update(c)
+        assert v.active().tolist() == exp, (W, calls, T)
+        n += 1
+    assert n >= 13
+
+
+def _fifo_reference(V, W, calls):
+    """an independent statement of the same queue: the members after the calls are the last W entries of the
+    list of all pushes, where a call's pushes are its distinct valid ids that are not among the last W pushes
+    made before the call (plain Python lists, recomputed from the whole history at every call)."""
+    pushes = []
+    for c in calls:
+        members = pushes[-W:] if W > 0 else []
+        new = []
+        for a in c:
+            if 0 <= a < V and a not in members and a not in new:
+                new.append(a)
+        pushes.extend(new)
+    return sorted(set(pushes[-W:]))
+
+
+def test_fifo_against_history_recomputation():
+    rng = np.random.default_rng(11)
+    for trial in range(300):
+        V = int(rng.integers(4, 40))
+        W = int(rng.integers(1, 12))
+        calls = [rng.integers(-2, V + 2, size=int(rng.integers(0, 3 * W + 2))).tolist() for _ in range(int(rng.integers(1, 9)))]
+        v = oracle.FifoVocab(V, W)
+        v.init(calls[0])
+        for i, c in enumerate(calls[1:], start=2):
+            v.update(c)
+            assert v.active().tolist() == _fifo_reference(V, W, calls[:i]), (V, W, calls[:i])
+        assert v.size() <= W
+
+
+def test_fifo_equals_window_when_nothing_repeats():
+    """with no repeated id anywhere in the stream the two readings coincide (the Eq. 4 oracle is pinned on its own)."""
+    rng = np.random.default_rng(12)
+    for trial in range(100):
+        V, W = 500, int(rng.integers(1, 60))
+        stream = rng.permutation(V)[: int(rng.integers(1, 200))].astype(np.int32)
+        cuts = np.sort(rng.integers(0, len(stream) + 1, size=4))
+        parts = np.split(stream, cuts)
+        T = rng.integers(0, V, size=5)
+        f, w = oracle.FifoVocab(V, W), oracle.Vocab(V, W)
+        f.init(parts[0], T)
+        w.init(parts[0], T)
+        for p in parts[1:]:
+            f.update(p)
+            w.update(p)
+            assert np.array_equal(f.active(), w.active())
+
+
+def test_fifo_invariants():
+    rng = np.random.default_rng(13)
+    V, W = 300, 40
+    zipf_like = lambda n: np.minimum((rng.pareto(1.1, size=n) * 3).astype(np.int32), V - 1)
+    f = oracle.FifoVocab(V, W)
+    f.init(zipf_like(30))
+    prev = set(f.active().tolist())
+    grown = True
+    for step in range(200):
+        new = zipf_like(int(rng.integers(0, 9)))
+        f.update(new)
+        cur = set(f.active().tolist())
+        assert len(cur) == f.size() <= W
+        if len(prev) + len(set(new.tolist()) - prev) <= W:
+            assert prev <= cur                                   # below capacity the vocabulary only grows
+        assert set(new.tolist()) - prev <= cur or len(set(new.tolist()) - prev) > W   # every new id gets in
+        f2_before = f.active().copy()
+        f.update(np.array(sorted(cur), np.int32))                # re-appending members changes nothing
+        assert np.array_equal(f.active(), f2_before)
+        prev = cur
+    # a candidate set is one call of its distinct valid ids in ascending order
+    a, b = oracle.FifoVocab(V, 5), oracle.FifoVocab(V, 5)
+    a.init([1, 2, 3])
+    b.init([1, 2, 3])
+    a.append_unique([9, 7, 7, -1, 2, 300, 8, 6])
+    b.update([6, 7, 8, 9])
+    assert np.array_equal(a.active(), b.active()) and a.active().tolist() == [3, 6, 7, 8, 9]

@@ -234,6 +234,26 @@ def main():
     closed = {"steps_per_s": round(KL / (loop_ms * 1e-3), 1), "us_per_step": round(loop_ms * 1e3 / KL, 2),
               "append_unique_us": round(app_us, 2), "topk_logprob_us": round(lp_us, 2), "active_after": n_loop[0]}
 
+    # The two readings of the vocabulary side by side (Eq. 4 window over the raw stream against the first-in
+    # first-out queue of distinct ids of Sec. 3.3 / the appendix): the same context and the same appended ids on
+    # two fresh states, |active| afterwards and the time per update over a graph of the real updates.
+    KP = min(K, 500)
+    policy_compare = {}
+    for name, pol in (("window", B.POLICY_WINDOW), ("fifo", B.POLICY_FIFO)):
+        st2 = B.State(V, d, Bn, seqs["window"], seqs["topk_cap"], M, k)
+        B.nanospec_set_stream_policy(st2.h, pol)
+        B.nanospec_vocab_init(st2.h, d_ctx, coff, d_T0, toff, stream)
+        n_init = [len(a) for a in st2.read_active()]
+        upd = lambda s_, cs: B.nanospec_vocab_update(st2.h, d_new, offs[s_], None, None, cs)
+        for s_ in range(Wm):
+            upd(s_, stream)
+        torch.cuda.synchronize()
+        us = timed(upd, Wm, KP) * 1e3 / KP
+        n_end = [len(a) for a in st2.read_active()]
+        policy_compare[name] = {"active_after_init": int(np.mean(n_init)), "active_after_updates": int(np.mean(n_end)),
+                                "update_us": round(us, 2)}
+        st2.close()
+
     # dense comparison point: full-vocabulary head + top-k over V
     dense = None
     if not args.no_dense:
@@ -292,6 +312,7 @@ def main():
         "kernels_us": {"vocab_update": round(upd_us, 2), "sparse_head": round(head_us, 2), "topk_remap": round(topk_us, 2)},
         "closed_loop": closed,
         "packed_buffer_variant": packed_variant,
+        "vocabulary_policies": policy_compare,
         "dense": dense,
         "cpu_baseline": cpu,
         "setup_s": round(time.time() - t0, 1),

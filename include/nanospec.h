@@ -94,6 +94,19 @@ NANOSPEC_API nanospec_status nanospec_create(nanospec_state** out, int32_t V, in
                                 int32_t window, int32_t topk_cap, int32_t m_cap, int32_t k_cap);
 NANOSPEC_API nanospec_status nanospec_destroy(nanospec_state* st);
 
+/* Which reading of the paper's vocabulary the state follows; takes effect at the next nanospec_vocab_init.
+ *   NANOSPEC_POLICY_WINDOW (default): Eq. 4 -- the window covers the last W_max entries of the raw stream,
+ *       repeats included; a token stays while any of its occurrences is inside the window.
+ *   NANOSPEC_POLICY_FIFO: the state management of Sec. 3.3 as the appendix on vocabulary evolution describes
+ *       it -- a first-in first-out queue of at most W_max distinct ids.  One call (init, update,
+ *       append_unique) pushes, in the order of their first occurrence, the ids that are valid, not members
+ *       when the call starts and not repeated inside the call; the oldest members leave first; a member
+ *       that is appended again keeps its place.  Ids outside [0,V) are skipped and flagged.
+ * Everything else (T, the ascending list, head, selection) is the same.  Errors: EINVAL. */
+#define NANOSPEC_POLICY_WINDOW 0
+#define NANOSPEC_POLICY_FIFO 1
+NANOSPEC_API nanospec_status nanospec_set_stream_policy(nanospec_state* st, int32_t policy);
+
 /* Stream initialisation, Eq. 2 and the first I of Alg. 1: for sequence b the stream becomes
  * ctx_ids[h_ctx_off[b] .. h_ctx_off[b+1]) (only its last `window` ids matter) and the candidate
  * set T becomes topk_ids[h_topk_off[b] .. h_topk_off[b+1]) (duplicates allowed, order
@@ -127,7 +140,7 @@ NANOSPEC_API nanospec_status nanospec_vocab_update(nanospec_state* st, const int
  * The same call finishes Eq. 2 on the device: after nanospec_vocab_init with the prompt, pass the [L][K_pre]
  * output of nanospec_dense_topk over the prefill logits (the tail of S^(0) is a de-duplicated union too).
  *   d_cand_ids : device int32 [batch][cand_stride]; cand_per_seq is bounded by the LDS of one workgroup:
- *                40800 - 12 * ceil(V/128) entries (28 776 at V = 128256); at least m_cap * k_cap.
+ *                39776 - 12 * ceil(V/128) entries (27 752 at V = 128256); at least m_cap * k_cap.
  * Errors: EINVAL (null, negative, stride < count), ECAPACITY (cand_per_seq above that bound).  Asynchronous; takes no host integers that
  * change from step to step, so one recorded HIP graph of a whole draft step can be replayed indefinitely. */
 NANOSPEC_API nanospec_status nanospec_vocab_append_unique(nanospec_state* st, const int32_t* d_cand_ids,

@@ -16,12 +16,13 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libnanospec.so")
 
 OK, EINVAL, ENOMEM, ECAPACITY, EHIP = 0, -1, -2, -3, -4
+POLICY_WINDOW, POLICY_FIFO = 0, 1
 DEV_BAD_ID = 1
 MAX_BATCH = 256
 
 EXPORTS = [
     "nanospec_status_string", "nanospec_state_layout", "nanospec_create", "nanospec_destroy",
-    "nanospec_vocab_init", "nanospec_vocab_update", "nanospec_vocab_append_unique", "nanospec_vocab_view", "nanospec_sparse_head",
+    "nanospec_set_stream_policy", "nanospec_vocab_init", "nanospec_vocab_update", "nanospec_vocab_append_unique", "nanospec_vocab_view", "nanospec_sparse_head",
     "nanospec_topk_remap", "nanospec_topk_logprob_remap", "nanospec_dense_head", "nanospec_dense_topk_workspace", "nanospec_dense_topk",
     "nanospec_calib_stream_read", "nanospec_calib_gather_read", "nanospec_last_device_error",
 ]
@@ -57,6 +58,7 @@ def lib() -> C.CDLL:
         L.nanospec_state_layout.argtypes = [i32] * 7 + [C.POINTER(Layout)]
         L.nanospec_create.argtypes = [C.POINTER(vp)] + [i32] * 7
         L.nanospec_destroy.argtypes = [vp]
+        L.nanospec_set_stream_policy.argtypes = [vp, i32]
         L.nanospec_vocab_init.argtypes = [vp, vp, i32p, vp, i32p, vp]
         L.nanospec_vocab_update.argtypes = [vp, vp, i32p, vp, i32p, vp]
         L.nanospec_vocab_append_unique.argtypes = [vp, vp, i32, i64, vp]
@@ -125,6 +127,10 @@ def nanospec_create(V, d, batch, window, topk_cap, m_cap, k_cap) -> int:
 
 def nanospec_destroy(st: int):
     _check(lib().nanospec_destroy(st), "nanospec_destroy")
+
+
+def nanospec_set_stream_policy(st, policy):
+    _check(lib().nanospec_set_stream_policy(st, policy), "nanospec_set_stream_policy")
 
 
 def nanospec_vocab_init(st, d_ctx_ids, h_ctx_off, d_topk_ids, h_topk_off, stream=None):

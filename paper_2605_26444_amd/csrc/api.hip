@@ -72,6 +72,7 @@ nanospec_status vocab_call(nanospec_state* st, const int32_t* d_new, const int32
   const int replace_T = (is_init || h_toff != nullptr) ? 1 : 0;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (is_init) {
+    st->policy = st->policy_next;
     if (launch_vocab_clear(st, s) != hipSuccess) return NANOSPEC_EHIP;
   }
   if (launch_vocab_apply(st, d_new, noff, d_topk, toff, replace_T, s) != hipSuccess) return NANOSPEC_EHIP;
@@ -109,6 +110,7 @@ nanospec_status nanospec_create(nanospec_state** out, int32_t V, int32_t d, int3
   if (!st) return NANOSPEC_ENOMEM;
   st->V = V; st->d = d; st->batch = batch; st->window = window;
   st->topk_cap = topk_cap; st->m_cap = m_cap; st->k_cap = k_cap;
+  st->policy = st->policy_next = NANOSPEC_POLICY_WINDOW;
   st->layout = L;
   if (hipGetDevice(&st->device) != hipSuccess) { delete st; return NANOSPEC_EHIP; }
   if (hipMalloc(reinterpret_cast<void**>(&st->base), L.total_bytes) != hipSuccess) {
@@ -157,6 +159,12 @@ nanospec_status nanospec_destroy(nanospec_state* st) {
   hipError_t e2 = hipHostFree(st->h_err_pinned);
   delete st;
   return (e1 == hipSuccess && e2 == hipSuccess) ? NANOSPEC_OK : NANOSPEC_EHIP;
+}
+
+nanospec_status nanospec_set_stream_policy(nanospec_state* st, int32_t policy) {
+  if (!st || (policy != NANOSPEC_POLICY_WINDOW && policy != NANOSPEC_POLICY_FIFO)) return NANOSPEC_EINVAL;
+  st->policy_next = policy;
+  return NANOSPEC_OK;
 }
 
 nanospec_status nanospec_vocab_init(nanospec_state* st, const int32_t* d_ctx_ids, const int32_t* h_ctx_off,

@@ -43,7 +43,8 @@ struct nanospec_state {
   char* topk_ws;            // two-pass top-k candidates
   int64_t partial_bytes, topk_ws_bytes;
   int32_t* h_err_pinned;    // pinned host word for reading the device flags
-  int vocab_lds_bytes, unique_lds_bytes, unique_cap;
+  int vocab_lds_bytes, unique_lds_bytes, unique_cap, fifo_lds_bytes;
+  int32_t policy, policy_next;   // vocabulary reading in force / chosen for the next init
 };
 
 namespace nanospec {

@@ -217,12 +217,152 @@ __global__ __launch_bounds__(kVocabThreads) void vocab_append_unique_kernel(Voca
   vocab_apply_body(p, b, ulist, a, nullptr, 0, 0, wb, tb, sc, bad);
 }
 
+// ---- second reading of the vocabulary: a first-in first-out queue of at most W distinct ids -------------
+// (paper Sec. 3.3: only candidates that are new to the vocabulary are pushed; appendix on vocabulary
+// evolution: it grows monotonically up to the capacity and is evicted first-in first-out.)
+// The ring holds the members in push order, the window bitmap is the membership test, the
+// multiplicity counters are not needed and their memory serves as the staging list of one call.
+//
+// One call = one batch: the ids that are valid, not members when the call starts and not seen earlier
+// in the call, in the order of their first occurrence; at most the last W of them are pushed after
+// the oldest members have made room.  src is walked in chunks of one workgroup: a thread's id is new if
+// neither bitmap (members, seen-in-this-call) has it and no earlier thread of the chunk holds the same
+// id; a ballot + prefix over the wavefronts gives every new id its place in the order.
+// wb/tb: LDS bitmaps (stores issued by this workgroup), ub: zeroed LDS bitmap, cl: kVocabThreads ints.
+__device__ __forceinline__ void fifo_apply_body(const VocabPtrs& p, int b, const int32_t* src, int a, const int32_t* ts,
+                                                int nt, int replace_T, uint32_t* wb, uint32_t* tb, uint32_t* ub, int* sc,
+                                                int32_t* cl, int bad) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nwords = p.nwords, V = p.V;
+  const int W = p.window < V ? p.window : V;                 // more than V distinct ids cannot exist
+  uint32_t* gw = p.wbit + (size_t)b * nwords;
+  uint32_t* gt = p.tbit + (size_t)b * nwords;
+  int32_t* ring = p.ring + (size_t)b * p.window;
+  int32_t* stage = reinterpret_cast<int32_t*>(p.cnt + (size_t)b * V);   // W slots, entry k of the call at k % W
+  const int pos = p.pos[b], fill = p.fill[b];
+
+  __syncthreads();                                           // LDS bitmaps complete
+  int nF = 0;
+  for (int c0 = 0; c0 < a; c0 += kVocabThreads) {
+    const int i = c0 + tid;
+    const int v = i < a ? src[i] : -1;
+    cl[tid] = v;
+    __syncthreads();
+    const bool ok = (unsigned)v < (unsigned)V;
+    if (i < a && !ok) bad = 1;
+    bool isnew = ok && !((wb[v >> 5] >> (v & 31)) & 1u) && !((ub[v >> 5] >> (v & 31)) & 1u);
+    if (isnew)
+      for (int j = 0; j < tid; ++j)
+        if (cl[j] == v) {
+          isnew = false;
+          break;
+        }
+    const unsigned long long bal = __ballot(isnew);
+    const int before = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) sc[wave] = __popcll(bal);
+    __syncthreads();
+    int off = nF, tot = 0;
+    for (int w = 0; w < kVocabThreads / 64; ++w) {
+      const int t = sc[w];
+      if (w < wave) off += t;
+      tot += t;
+    }
+    nF += tot;
+    if (isnew) {
+      atomicOr(&ub[v >> 5], 1u << (v & 31));
+      const int k = off + before;
+      if (k >= nF - W) stage[k % W] = v;                     // older entries of the call can never stay
+    }
+    __syncthreads();                                         // cl, sc and ub are reused by the next chunk
+  }
+  const int keep = nF < W ? nF : W;
+  int n_evict = fill + keep - W;
+  if (n_evict < 0) n_evict = 0;
+  int oldest = pos - fill;
+  if (oldest < 0) oldest += W;
+  for (int i = tid; i < n_evict; i += kVocabThreads) {
+    const int e = ring[(oldest + i) % W];
+    atomicAnd(&wb[e >> 5], ~(1u << (e & 31)));
+  }
+  __syncthreads();                                           // slots about to be overwritten have been read
+  for (int i = tid; i < keep; i += kVocabThreads) {
+    const int v = stage[(nF - keep + i) % W];
+    ring[(pos + i) % W] = v;
+    atomicOr(&wb[v >> 5], 1u << (v & 31));
+  }
+  if (replace_T) {
+    for (int i = tid; i < nt; i += kVocabThreads) {
+      const int t = ts[i];
+      if ((unsigned)t < (unsigned)V) atomicOr(&tb[t >> 5], 1u << (t & 31));
+      else bad = 1;
+    }
+  }
+  __syncthreads();
+  const int total = compact_bitmap([&](int i) { return wb[i] | tb[i]; }, nwords, p.ids + (size_t)b * p.cap, p.cap, sc, tid);
+  for (int i = tid * 4; i < nwords; i += kVocabThreads * 4) {
+    *reinterpret_cast<uint4*>(gw + i) = *reinterpret_cast<const uint4*>(wb + i);
+    if (replace_T) *reinterpret_cast<uint4*>(gt + i) = *reinterpret_cast<const uint4*>(tb + i);
+  }
+  if (tid == 0) {
+    p.n[b] = total < p.cap ? total : p.cap;
+    p.pos[b] = (pos + keep) % W;
+    const int nf = fill + keep;
+    p.fill[b] = nf < W ? nf : W;
+  }
+  if (bad) atomicOr(p.err, (int)NANOSPEC_DEV_BAD_ID);
+}
+
+__global__ __launch_bounds__(kVocabThreads) void vocab_fifo_kernel(VocabPtrs p, const int32_t* __restrict__ new_ids,
+                                                                   Offsets noff, const int32_t* __restrict__ topk,
+                                                                   Offsets toff, int replace_T) {
+  extern __shared__ uint32_t lds[];
+  const int b = blockIdx.x, tid = threadIdx.x, nwords = p.nwords;
+  uint32_t* wb = lds;
+  uint32_t* tb = lds + nwords;
+  int* sc = reinterpret_cast<int*>(tb + nwords);
+  uint32_t* ub = reinterpret_cast<uint32_t*>(sc + 32);
+  int32_t* cl = reinterpret_cast<int32_t*>(ub + nwords);
+  load_bitmaps(p, b, wb, tb, replace_T);
+  for (int i = tid * 4; i < nwords; i += kVocabThreads * 4) *reinterpret_cast<uint4*>(ub + i) = make_uint4(0, 0, 0, 0);
+  fifo_apply_body(p, b, new_ids + noff.v[b], noff.v[b + 1] - noff.v[b], topk + toff.v[b], toff.v[b + 1] - toff.v[b],
+                  replace_T, wb, tb, ub, sc, cl, 0);
+}
+
+// candidate set built on the device, queue reading: distinct valid candidates in ascending order, then one batch
+__global__ __launch_bounds__(kVocabThreads) void vocab_fifo_append_unique_kernel(VocabPtrs p, const int32_t* __restrict__ cand,
+                                                                                 int per_seq, int64_t stride, int ucap) {
+  extern __shared__ uint32_t lds[];
+  const int b = blockIdx.x, tid = threadIdx.x, nwords = p.nwords;
+  uint32_t* wb = lds;
+  uint32_t* tb = lds + nwords;
+  int* sc = reinterpret_cast<int*>(tb + nwords);
+  uint32_t* ub = reinterpret_cast<uint32_t*>(sc + 32);
+  int32_t* cl = reinterpret_cast<int32_t*>(ub + nwords);
+  int32_t* ulist = cl + kVocabThreads;
+  load_bitmaps(p, b, wb, tb, 0);
+  for (int i = tid * 4; i < nwords; i += kVocabThreads * 4) *reinterpret_cast<uint4*>(ub + i) = make_uint4(0, 0, 0, 0);
+  __syncthreads();
+  int bad = 0;
+  for (int i = tid; i < per_seq; i += kVocabThreads) {
+    const int v = cand[b * stride + i];
+    if ((unsigned)v < (unsigned)p.V) atomicOr(&ub[v >> 5], 1u << (v & 31));
+    else if (v != -1) bad = 1;
+  }
+  __syncthreads();
+  int a = compact_bitmap([&](int i) { return ub[i]; }, nwords, ulist, ucap, sc, tid);
+  a = a < ucap ? a : ucap;
+  __syncthreads();
+  for (int i = tid * 4; i < nwords; i += kVocabThreads * 4) *reinterpret_cast<uint4*>(ub + i) = make_uint4(0, 0, 0, 0);
+  fifo_apply_body(p, b, ulist, a, nullptr, 0, 0, wb, tb, ub, sc, cl, bad);
+}
+
 hipError_t vocab_configure(nanospec_state* st) {
   st->vocab_lds_bytes = (2 * st->vp.nwords + 32) * 4;
   // candidates per call are bounded by what is left of the 160 KB of LDS after three bitmaps
-  st->unique_cap = (160 * 1024 - 512) / 4 - (3 * st->vp.nwords + 32);
+  st->unique_cap = (160 * 1024 - 512) / 4 - (3 * st->vp.nwords + 32 + kVocabThreads);
   if (st->unique_cap < st->m_cap * st->k_cap) return hipErrorInvalidValue;
-  st->unique_lds_bytes = (3 * st->vp.nwords + 32 + st->unique_cap) * 4;
+  st->unique_lds_bytes = (3 * st->vp.nwords + 32 + kVocabThreads + st->unique_cap) * 4;
+  st->fifo_lds_bytes = (3 * st->vp.nwords + 32 + kVocabThreads) * 4;
   hipError_t e = hipSuccess;
   if (st->vocab_lds_bytes > 48 * 1024)
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(vocab_apply_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -230,6 +370,12 @@ hipError_t vocab_configure(nanospec_state* st) {
   if (e == hipSuccess && st->unique_lds_bytes > 48 * 1024)
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(vocab_append_unique_kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize, st->unique_lds_bytes);
+  if (e == hipSuccess && st->unique_lds_bytes > 48 * 1024)
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(vocab_fifo_append_unique_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, st->unique_lds_bytes);
+  if (e == hipSuccess && st->fifo_lds_bytes > 48 * 1024)
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(vocab_fifo_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            st->fifo_lds_bytes);
   return e;
 }
 
@@ -243,6 +389,10 @@ hipError_t launch_vocab_clear(const nanospec_state* st, hipStream_t s) {
 
 hipError_t launch_vocab_apply(const nanospec_state* st, const int32_t* d_new, const Offsets& noff,
                               const int32_t* d_topk, const Offsets& toff, int replace_T, hipStream_t s) {
+  if (st->policy == NANOSPEC_POLICY_FIFO) {
+    vocab_fifo_kernel<<<st->batch, kVocabThreads, st->fifo_lds_bytes, s>>>(st->vp, d_new, noff, d_topk, toff, replace_T);
+    return hipGetLastError();
+  }
   vocab_apply_kernel<<<st->batch, kVocabThreads, st->vocab_lds_bytes, s>>>(st->vp, d_new, noff, d_topk, toff,
                                                                            replace_T);
   return hipGetLastError();
@@ -251,6 +401,11 @@ hipError_t launch_vocab_apply(const nanospec_state* st, const int32_t* d_new, co
 hipError_t launch_vocab_append_unique(const nanospec_state* st, const int32_t* d_cand, int per_seq, int64_t stride,
                                       hipStream_t s) {
   const int ucap = per_seq < st->V ? per_seq : st->V;       // no more distinct ids than candidates or tokens
+  if (st->policy == NANOSPEC_POLICY_FIFO) {
+    const int flds = (3 * st->vp.nwords + 32 + kVocabThreads + ucap) * 4;
+    vocab_fifo_append_unique_kernel<<<st->batch, kVocabThreads, flds, s>>>(st->vp, d_cand, per_seq, stride, ucap);
+    return hipGetLastError();
+  }
   const int lds = (3 * st->vp.nwords + 32 + ucap) * 4;
   vocab_append_unique_kernel<<<st->batch, kVocabThreads, lds, s>>>(st->vp, d_cand, per_seq, stride, ucap);
   return hipGetLastError();

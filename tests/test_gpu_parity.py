@@ -523,3 +523,89 @@ def test_calibration_reads_run_and_touch_nothing():
     assert np.array_equal(dW.view(torch.int16).cpu().numpy().view(np.uint16), W)
     assert B.nanospec_last_device_error(st.h) == 0
     st.close()
+
+
+# ---- second reading of the vocabulary: first-in first-out queue of distinct ids (NANOSPEC_POLICY_FIFO)
+
+def test_fifo_policy_worked_and_edge_cases():
+    V = 1000
+    st = B.State(V, 64, 1, 4, 4, 2, 4)
+    B.nanospec_set_stream_policy(st.h, B.POLICY_FIFO)
+    orc = oracle.FifoVocab(V, 4)
+    B.nanospec_vocab_init(st.h, dev(np.array([5, 6, 5, 7], np.int32)), [0, 4], dev(np.array([90], np.int32)), [0, 1])
+    orc.init([5, 6, 5, 7], [90])
+    assert st.read_active()[0].tolist() == [5, 6, 7, 90]
+    for new in ([6, 8, 9], [5], [], [5, 5, 5], [1, 2, 3, 4, 10, 11], [999, 1000, -1, 0]):
+        B.nanospec_vocab_update(st.h, dev_ids(np.array(new, np.int32)), [0, len(new)])
+        orc.update(new)
+        assert np.array_equal(st.read_active()[0], orc.active()), new
+    assert B.nanospec_last_device_error(st.h) == B.DEV_BAD_ID       # 1000 and -1 were skipped and flagged
+    assert st.read_active()[0].tolist() == [0, 10, 11, 90, 999]
+    # switching back takes effect at the next init
+    B.nanospec_set_stream_policy(st.h, B.POLICY_WINDOW)
+    B.nanospec_vocab_init(st.h, dev(np.array([1, 4, 4, 4, 4, 4], np.int32)), [0, 6], None, [0, 0])
+    assert st.read_active()[0].tolist() == [4]                      # raw-stream window of 4: (4 4 4 4)
+    B.nanospec_set_stream_policy(st.h, B.POLICY_FIFO)
+    B.nanospec_vocab_init(st.h, dev(np.array([1, 4, 4, 4, 4, 4], np.int32)), [0, 6], None, [0, 0])
+    assert st.read_active()[0].tolist() == [1, 4]
+    assert B.lib().nanospec_set_stream_policy(st.h, 7) == B.EINVAL
+    st.close()
+
+
+@pytest.mark.parametrize("W,vals,big", [(37, 300, 90), (3000, 6000, 5000), (64, 100000, 2500)])
+def test_fifo_policy_fuzz_ragged_batch(W, vals, big):
+    """windows smaller and larger than one workgroup's chunk, appends longer than the queue and longer than a
+    chunk (several passes, wrap of the staging list), T replaced every third step."""
+    rng = np.random.default_rng(W)
+    V, Bn = 100000, 5
+    st = B.State(V, 64, Bn, W, 20, 2, 4)
+    B.nanospec_set_stream_policy(st.h, B.POLICY_FIFO)
+    orc = [oracle.FifoVocab(V, W) for _ in range(Bn)]
+    ctx = [rng.integers(0, vals, size=int(rng.integers(0, big))).astype(np.int32) for _ in range(Bn)]
+    T = [rng.integers(0, V, size=int(rng.integers(0, 21))).astype(np.int32) for _ in range(Bn)]
+    f, off = csr(ctx)
+    tf, toff = csr(T)
+    B.nanospec_vocab_init(st.h, dev_ids(f), off, dev_ids(tf), toff)
+    for b in range(Bn):
+        orc[b].init(ctx[b], T[b])
+    act = st.read_active()
+    for b in range(Bn):
+        assert np.array_equal(act[b], orc[b].active()), ("init", b)
+    for step in range(40):
+        new = [rng.integers(0, vals, size=int(rng.integers(0, big if step % 10 == 0 else 9))).astype(np.int32) for _ in range(Bn)]
+        f, off = csr(new)
+        if step % 3 == 0:
+            T = [rng.integers(0, V, size=int(rng.integers(0, 21))).astype(np.int32) for _ in range(Bn)]
+            tf, toff = csr(T)
+            B.nanospec_vocab_update(st.h, dev_ids(f), off, dev_ids(tf), toff)
+        else:
+            B.nanospec_vocab_update(st.h, dev_ids(f), off)
+        act = st.read_active()
+        for b in range(Bn):
+            orc[b].update(new[b], T[b] if step % 3 == 0 else None)
+            assert np.array_equal(act[b], orc[b].active()), (step, b)
+    assert B.nanospec_last_device_error(st.h) == 0
+    st.close()
+
+
+def test_fifo_policy_device_side_feedback():
+    """append_unique under the queue reading: a candidate set is one batch of its distinct valid ids, ascending."""
+    rng = np.random.default_rng(77)
+    V, W, Bn, per = 3000, 50, 3, 24
+    st = B.State(V, 64, Bn, W, 0, 4, 6)
+    B.nanospec_set_stream_policy(st.h, B.POLICY_FIFO)
+    orc = [oracle.FifoVocab(V, W) for _ in range(Bn)]
+    ctx = [rng.integers(0, 200, size=30).astype(np.int32) for _ in range(Bn)]
+    f, off = csr(ctx)
+    B.nanospec_vocab_init(st.h, dev(f), off, None, np.zeros(Bn + 1, np.int32))
+    for b in range(Bn):
+        orc[b].init(ctx[b])
+    for step in range(30):
+        cand = rng.integers(-1, 260, size=(Bn, per)).astype(np.int32)      # -1 = padding
+        B.nanospec_vocab_append_unique(st.h, dev(cand), per, per)
+        act = st.read_active()
+        for b in range(Bn):
+            orc[b].append_unique(cand[b])
+            assert np.array_equal(act[b], orc[b].active()), (step, b)
+    assert B.nanospec_last_device_error(st.h) == 0
+    st.close()

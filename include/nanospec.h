@@ -89,6 +89,9 @@ NANOSPEC_API nanospec_status nanospec_state_layout(int32_t V, int32_t d, int32_t
  *   window    W_max of Eq. 4                               topk_cap largest |T| per sequence
  *   m_cap     largest number of draft hidden rows per sequence and call
  *   k_cap     largest k of nanospec_topk_remap (<= 64)
+ * Limits: batch <= NANOSPEC_MAX_BATCH; min(window + topk_cap, V) <= 262144 (16 top-k chunks); the vocabulary
+ * kernels keep three V-bit bitmaps in one workgroup's LDS, which bounds V at about 420 000.
+ * Errors: EINVAL (null, a size < 1, d % 8 != 0, a limit above exceeded), ENOMEM, EHIP.
  * Synchronous (allocates).  The state starts empty: stream length 0, T empty, I empty. */
 NANOSPEC_API nanospec_status nanospec_create(nanospec_state** out, int32_t V, int32_t d, int32_t batch,
                                 int32_t window, int32_t topk_cap, int32_t m_cap, int32_t k_cap);

@@ -19,6 +19,8 @@ bool fill_layout(int32_t V, int32_t d, int32_t batch, int32_t window, int32_t to
       m_cap < 1 || k_cap < 1 || k_cap > kMaxK)
     return false;
   const int64_t nwords = round_up((V + 31) / 32, 4);
+  // three V-bit bitmaps, a 1024-entry chunk and m_cap*k_cap candidates share one workgroup's 160 KB of LDS
+  if (3 * nwords + 32 + kVocabThreads + (int64_t)m_cap * k_cap > (160 * 1024 - 512) / 4) return false;
   int64_t maxn = (int64_t)window + topk_cap;
   if (maxn > V) maxn = V;
   const int64_t cap = round_up(maxn, 64);

@@ -59,3 +59,13 @@ def test_layout_rejects_bad_shapes(lib):
 def test_capacity_is_bounded_by_vocabulary(lib):
     L = B.nanospec_state_layout(100, 8, 1, 5000, 300, 1, 1)
     assert L.capacity == 128                                                   # min(window+topk_cap, V) -> 64-multiple
+
+
+def test_layout_rejects_vocabularies_beyond_the_lds_limit():
+    import ctypes as C
+    L = B.lib()
+    lay = B.Layout()
+    assert L.nanospec_state_layout(420000, 4096, 1, 1024, 2727, 8, 10, C.byref(lay)) == B.OK
+    assert L.nanospec_state_layout(430000, 4096, 1, 1024, 2727, 8, 10, C.byref(lay)) == B.EINVAL
+    assert L.nanospec_state_layout(128256, 4096, 1, 300000, 0, 8, 10, C.byref(lay)) == B.OK         # capacity clamps to V
+    assert L.nanospec_state_layout(400000, 4096, 1, 300000, 0, 8, 10, C.byref(lay)) == B.EINVAL     # > 16 top-k chunks

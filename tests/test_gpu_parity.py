@@ -609,3 +609,69 @@ def test_fifo_policy_device_side_feedback():
             assert np.array_equal(act[b], orc[b].active()), (step, b)
     assert B.nanospec_last_device_error(st.h) == 0
     st.close()
+
+
+@pytest.mark.parametrize("policy", [0, 1])
+def test_limits_odd_vocabulary_full_membership_and_widest_k(policy):
+    """V not a multiple of 32, window larger than V (capacity clamps to V), every id active, k = 64, d = 8."""
+    V, d, M, k = 1001, 8, 3, 64
+    W = synth.normal_bf16(31, 0, (V, d), 0.02, threads=1)
+    H = synth.normal_bf16(31, 1, (M, d), 1.0, threads=1)
+    st = B.State(V, d, 1, 5000, 0, M, k)
+    B.nanospec_set_stream_policy(st.h, policy)
+    assert st.capacity == 1024
+    rng = np.random.default_rng(policy)
+    ctx = np.concatenate([rng.permutation(V), rng.integers(0, V, size=700)]).astype(np.int32)
+    B.nanospec_vocab_init(st.h, dev(ctx), [0, len(ctx)], None, [0, 0])
+    act = st.read_active()[0]
+    assert np.array_equal(act, np.arange(V, dtype=np.int32))
+    logits = torch.empty((1, M, st.capacity), dtype=torch.float32, device="cuda")
+    oi = torch.empty((1, M, k), dtype=torch.int32, device="cuda")
+    ov = torch.empty((1, M, k), dtype=torch.float32, device="cuda")
+    B.nanospec_sparse_head(st.h, dev_bf16(W), dev_bf16(H), M, logits)
+    B.nanospec_topk_remap(st.h, logits, M, k, oi, ov)
+    torch.cuda.synchronize()
+    g = logits.cpu().numpy()[0]
+    o32, o64 = oracle.head(W, H, ids=act)
+    assert_logits_close(g[:, :V], o64, o32)
+    for m in range(M):
+        ei, ev = oracle.topk(g[m, :V], act, k)
+        assert np.array_equal(oi.cpu().numpy()[0, m], ei) and np.array_equal(ov.cpu().numpy()[0, m], ev)
+    st.close()
+
+
+def test_limits_largest_batch():
+    """NANOSPEC_MAX_BATCH sequences in one state: ragged contexts, one update, head and selection for all."""
+    V, d, M, k, Bn, Wn = 3000, 64, 2, 5, 256, 20
+    W = synth.normal_bf16(41, 0, (V, d), 0.02, threads=1)
+    H = synth.normal_bf16(41, 1, (Bn, M, d), 1.0, threads=1)
+    st = B.State(V, d, Bn, Wn, 3, M, k)
+    rng = np.random.default_rng(41)
+    ctx = [rng.integers(0, V, size=int(rng.integers(0, 40))).astype(np.int32) for _ in range(Bn)]
+    T = [rng.integers(0, V, size=int(rng.integers(0, 4))).astype(np.int32) for _ in range(Bn)]
+    new = [rng.integers(0, V, size=int(rng.integers(0, 6))).astype(np.int32) for _ in range(Bn)]
+    f, off = csr(ctx)
+    tf, toff = csr(T)
+    nf, noff = csr(new)
+    B.nanospec_vocab_init(st.h, dev_ids(f), off, dev_ids(tf), toff)
+    B.nanospec_vocab_update(st.h, dev_ids(nf), noff)
+    logits = torch.empty((Bn, M, st.capacity), dtype=torch.float32, device="cuda")
+    oi = torch.empty((Bn, M, k), dtype=torch.int32, device="cuda")
+    B.nanospec_sparse_head(st.h, dev_bf16(W), dev_bf16(H), M, logits)
+    B.nanospec_topk_remap(st.h, logits, M, k, oi, None)
+    torch.cuda.synchronize()
+    act = st.read_active()
+    g, gi = logits.cpu().numpy(), oi.cpu().numpy()
+    for b in range(Bn):
+        o = oracle.Vocab(V, Wn)
+        o.init(ctx[b], T[b])
+        o.update(new[b])
+        exp = o.active()
+        assert np.array_equal(act[b], exp), b
+        if len(exp):
+            o32, o64 = oracle.head(W, H[b], ids=exp)
+            assert_logits_close(g[b][:, :len(exp)], o64, o32, what=f"seq {b}")
+        for m in range(M):
+            ei, _ = oracle.topk(g[b, m, :len(exp)], exp, k)
+            assert np.array_equal(gi[b, m], ei), (b, m)
+    st.close()

@@ -30,12 +30,20 @@ __global__ __launch_bounds__(256) void vocab_clear_kernel(VocabPtrs p, int batch
   }
 }
 
-__device__ __forceinline__ int wave_incl_scan(int x, int lane) {
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    int y = __shfl_up(x, o);
-    if (lane >= o) x += y;
-  }
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_add_int(int x) {
+  return x + __builtin_amdgcn_update_dpp(0, x, CTRL, ROW_MASK, 0xf, false);   // lanes without a source add 0
+}
+
+// inclusive prefix sum over the 64 lanes: Hillis-Steele inside each row of 16 (row_shr 1/2/4/8), then the
+// row totals carried across (row_bcast:15 into rows 1 and 3, row_bcast:31 into rows 2 and 3)
+__device__ __forceinline__ int wave_incl_scan(int x, int /*lane*/) {
+  x = dpp_add_int<0x111, 0xf>(x);
+  x = dpp_add_int<0x112, 0xf>(x);
+  x = dpp_add_int<0x114, 0xf>(x);
+  x = dpp_add_int<0x118, 0xf>(x);
+  x = dpp_add_int<0x142, 0xa>(x);
+  x = dpp_add_int<0x143, 0xc>(x);
   return x;
 }
 

@@ -48,33 +48,59 @@ __device__ __forceinline__ int wave_incl_scan(int x, int /*lane*/) {
 }
 
 // Ascending compaction of a bitmap held in LDS: popcount per thread, workgroup exclusive scan,
-// emission in id order.  word(i) yields bitmap word i; out[0..total) receives the ids (at most cap
-// are stored).  Every thread of the workgroup must call it, after a barrier that separates it from
-// any earlier use of sc; returns the number of set bits.
-template <typename WordFn>
-__device__ __forceinline__ int compact_bitmap(WordFn word, int nwords, int32_t* out, int cap, int* sc, int tid) {
+// emission in id order.  word4(i) yields bitmap words i..i+3 (i a multiple of 4); out[0..total) receives
+// the ids (at most cap are stored).  Every thread of the workgroup must call it, after a barrier that
+// separates it from any earlier use of sc; returns the number of set bits.  A thread's words (4 for
+// vocabularies up to 131072 ids, 8 up to 262144) stay in registers between the count and the emission.
+template <typename Word4Fn>
+__device__ __forceinline__ int compact_bitmap(Word4Fn word4, int nwords, int32_t* out, int cap, int* sc, int tid) {
   const int lane = tid & 63, wave = tid >> 6;
   const int wpt = (((nwords + kVocabThreads - 1) / kVocabThreads) + 3) & ~3;
   const int w0 = tid * wpt;
+  constexpr int kKeep = 8;
+  uint32_t keep[kKeep];
   int mine = 0;
-  for (int i = w0; i < w0 + wpt && i < nwords; ++i) mine += __popc(word(i));
+#pragma unroll
+  for (int c = 0; c < kKeep / 4; ++c) {
+    const int i = w0 + 4 * c;
+    uint4 x = make_uint4(0, 0, 0, 0);
+    if (4 * c < wpt && i < nwords) x = word4(i);
+    keep[4 * c] = x.x;
+    keep[4 * c + 1] = x.y;
+    keep[4 * c + 2] = x.z;
+    keep[4 * c + 3] = x.w;
+    mine += __popc(x.x) + __popc(x.y) + __popc(x.z) + __popc(x.w);
+  }
+  for (int i = w0 + kKeep; i < w0 + wpt && i < nwords; i += 4) {   // vocabularies above 262144 ids
+    const uint4 x = word4(i);
+    mine += __popc(x.x) + __popc(x.y) + __popc(x.z) + __popc(x.w);
+  }
   const int incl = wave_incl_scan(mine, lane);
   if (lane == 63) sc[wave] = incl;
   __syncthreads();
   int off = incl - mine, total = 0;
-  for (int w = 0; w < kVocabThreads / 64; ++w) {
-    const int t = sc[w];
-    if (w < wave) off += t;
-    total += t;
+#pragma unroll
+  for (int w = 0; w < kVocabThreads / 64; w += 4) {
+    const int4 t = *reinterpret_cast<const int4*>(sc + w);
+    off += (w < wave ? t.x : 0) + (w + 1 < wave ? t.y : 0) + (w + 2 < wave ? t.z : 0) + (w + 3 < wave ? t.w : 0);
+    total += t.x + t.y + t.z + t.w;
   }
-  for (int i = w0; i < w0 + wpt && i < nwords; ++i) {
-    uint32_t x = word(i);
+  auto emit = [&](uint32_t x, int base) {
     while (x) {
       const int bit = __ffs(x) - 1;
-      if (off < cap) out[off] = i * 32 + bit;
+      if (off < cap) out[off] = base + bit;
       ++off;
       x &= x - 1;
     }
+  };
+#pragma unroll
+  for (int q = 0; q < kKeep; ++q) emit(keep[q], (w0 + q) * 32);   // words past the end are zero
+  for (int i = w0 + kKeep; i < w0 + wpt && i < nwords; i += 4) {
+    const uint4 x = word4(i);
+    emit(x.x, i * 32);
+    emit(x.y, (i + 1) * 32);
+    emit(x.z, (i + 2) * 32);
+    emit(x.w, (i + 3) * 32);
   }
   return total;
 }
@@ -155,7 +181,11 @@ __device__ __forceinline__ void vocab_apply_body(const VocabPtrs& p, int b, cons
   __syncthreads();
 
   // compaction of (window | T)
-  const int total = compact_bitmap([&](int i) { return wb[i] | tb[i]; }, nwords, p.ids + (size_t)b * p.cap, p.cap, sc, tid);
+  const int total = compact_bitmap(
+      [&](int i) {
+        const uint4 a = *reinterpret_cast<const uint4*>(wb + i), c = *reinterpret_cast<const uint4*>(tb + i);
+        return make_uint4(a.x | c.x, a.y | c.y, a.z | c.z, a.w | c.w);
+      }, nwords, p.ids + (size_t)b * p.cap, p.cap, sc, tid);
   // bitmaps back to HBM
   for (int i = tid * 4; i < nwords; i += kVocabThreads * 4) {
     *reinterpret_cast<uint4*>(gw + i) = *reinterpret_cast<const uint4*>(wb + i);
@@ -219,7 +249,7 @@ __global__ __launch_bounds__(kVocabThreads) void vocab_append_unique_kernel(Voca
     else if (v != -1) bad = 1;
   }
   __syncthreads();
-  int a = compact_bitmap([&](int i) { return ub[i]; }, nwords, ulist, ucap, sc, tid);
+  int a = compact_bitmap([&](int i) { return *reinterpret_cast<const uint4*>(ub + i); }, nwords, ulist, ucap, sc, tid);
   a = a < ucap ? a : ucap;
   __syncthreads();
   vocab_apply_body(p, b, ulist, a, nullptr, 0, 0, wb, tb, sc, bad);
@@ -306,7 +336,11 @@ __device__ __forceinline__ void fifo_apply_body(const VocabPtrs& p, int b, const
     }
   }
   __syncthreads();
-  const int total = compact_bitmap([&](int i) { return wb[i] | tb[i]; }, nwords, p.ids + (size_t)b * p.cap, p.cap, sc, tid);
+  const int total = compact_bitmap(
+      [&](int i) {
+        const uint4 a = *reinterpret_cast<const uint4*>(wb + i), c = *reinterpret_cast<const uint4*>(tb + i);
+        return make_uint4(a.x | c.x, a.y | c.y, a.z | c.z, a.w | c.w);
+      }, nwords, p.ids + (size_t)b * p.cap, p.cap, sc, tid);
   for (int i = tid * 4; i < nwords; i += kVocabThreads * 4) {
     *reinterpret_cast<uint4*>(gw + i) = *reinterpret_cast<const uint4*>(wb + i);
     if (replace_T) *reinterpret_cast<uint4*>(gt + i) = *reinterpret_cast<const uint4*>(tb + i);
@@ -357,7 +391,7 @@ __global__ __launch_bounds__(kVocabThreads) void vocab_fifo_append_unique_kernel
     else if (v != -1) bad = 1;
   }
   __syncthreads();
-  int a = compact_bitmap([&](int i) { return ub[i]; }, nwords, ulist, ucap, sc, tid);
+  int a = compact_bitmap([&](int i) { return *reinterpret_cast<const uint4*>(ub + i); }, nwords, ulist, ucap, sc, tid);
   a = a < ucap ? a : ucap;
   __syncthreads();
   for (int i = tid * 4; i < nwords; i += kVocabThreads * 4) *reinterpret_cast<uint4*>(ub + i) = make_uint4(0, 0, 0, 0);

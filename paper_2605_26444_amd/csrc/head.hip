@@ -67,6 +67,13 @@ __global__ __launch_bounds__(256) void head_generic_kernel(const uint16_t* __res
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// sum over the four lanes of a quad, in every lane of it (DPP quad_perm: neighbours 1 apart, then 2 apart)
+__device__ __forceinline__ float quad_sum(float x) {
+  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xf, 0xf, true));   // quad_perm:[1,0,3,2]
+  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xf, 0xf, true));   // quad_perm:[2,3,0,1]
+  return x;
+}
+
 // Matrix-core kernel for few hidden rows (M <= 16) when d needs several K-iterations: same operand
 // layout as head_quad_kernel below, but every wavefront fetches its own hidden-row operands and
 // nothing goes through LDS except the final K-slice sum, so the K loop carries no barrier.
@@ -167,8 +174,7 @@ __global__ __launch_bounds__(64 * NW) void head_quad_private_kernel(const uint16
     for (int mt = 0; mt < MT; ++mt) {
       const f32x4 a = acc[rt][mt];
       float x = part == 0 ? a[0] : (part == 1 ? a[1] : (part == 2 ? a[2] : a[3]));
-      x += __shfl_xor(x, 1);
-      x += __shfl_xor(x, 2);
+      x = quad_sum(x);
       if (part == 0) red[w][(rt * MT + mt) * 16 + q * 4 + orow] = x;     // (row q of the tile, hidden row orow)
     }
   __syncthreads();
@@ -311,8 +317,7 @@ __global__ __launch_bounds__(256 * NRG) void head_quad_kernel(const uint16_t* __
     for (int mt = 0; mt < MT; ++mt) {
       const f32x4 a = acc[rt][mt];
       float x = part == 0 ? a[0] : (part == 1 ? a[1] : (part == 2 ? a[2] : a[3]));
-      x += __shfl_xor(x, 1);
-      x += __shfl_xor(x, 2);
+      x = quad_sum(x);
       if (part == 0) red[w * NOUT + (rt * MT + mt) * 16 + q * 4 + orow] = x;   // (tile row q, hidden row orow)
     }
   __syncthreads();

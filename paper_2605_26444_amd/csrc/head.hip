@@ -250,7 +250,14 @@ __global__ __launch_bounds__(256 * NRG) void head_quad_kernel(const uint16_t* __
   // past the end therefore run through with their weight loads masked off.)
   int idr[RPG];
 #pragma unroll
-  for (int r = 0; r < RPG; ++r) idr[r] = ids ? ids[b * ids_stride + j0 + r] : j0 + r;
+  for (int rt = 0; rt < RT; ++rt) {                       // one 16-byte load per four rows (j0 and the row stride are multiples of 4)
+    const int4 v = ids ? *reinterpret_cast<const int4*>(ids + b * ids_stride + j0 + rt * 4)
+                       : make_int4(j0 + rt * 4, j0 + rt * 4 + 1, j0 + rt * 4 + 2, j0 + rt * 4 + 3);
+    idr[rt * 4] = v.x;
+    idr[rt * 4 + 1] = v.y;
+    idr[rt * 4 + 2] = v.z;
+    idr[rt * 4 + 3] = v.w;
+  }
   const int n = n_dev ? n_dev[b] : n_fixed;
 
   auto load_h = [&](int kb, u32x4(&hv)[HPW]) {

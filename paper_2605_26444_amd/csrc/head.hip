@@ -123,7 +123,14 @@ __global__ __launch_bounds__(64 * NW) void head_quad_private_kernel(const uint16
   // product is never stored.
   int idr[ROWS];
 #pragma unroll
-  for (int r = 0; r < ROWS; ++r) idr[r] = ids ? ids[b * ids_stride + j0 + r] : j0 + r;
+  for (int rt = 0; rt < RT; ++rt) {
+    const int4 v = ids ? *reinterpret_cast<const int4*>(ids + b * ids_stride + j0 + rt * 4)
+                       : make_int4(j0 + rt * 4, j0 + rt * 4 + 1, j0 + rt * 4 + 2, j0 + rt * 4 + 3);
+    idr[rt * 4] = v.x;
+    idr[rt * 4 + 1] = v.y;
+    idr[rt * 4 + 2] = v.z;
+    idr[rt * 4 + 3] = v.w;
+  }
   const int n = n_dev ? n_dev[b] : n_fixed;
   // hidden rows of the first K-iteration depend on the arguments only: they stream in from L2
   // while the ids are still on their way

@@ -89,7 +89,9 @@ __device__ __forceinline__ void wave_select(float (&v)[EPT], int k, int lane, Em
 }
 
 // One workgroup of NW wavefronts selects the k best of elements [c*CH, (c+1)*CH) of row (b, m),
-// CH = NW*64*EPT.  FINAL: write global ids / values; else (value, position) for the merge kernel.
+// CH = NW*64*EPT.  FINAL: write global ids / values; else (value, position) for the merge kernel --
+// unless the whole row fits the first chunk (n <= CH, known only on the device): then chunk 0 writes the
+// final result itself, the other chunks leave at once and the merge kernel has nothing to do.
 template <int EPT, int NW, bool FINAL, bool LSE>
 __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __restrict__ logits, int64_t ld,
                                                              const int32_t* __restrict__ ids, int64_t ids_stride,
@@ -131,7 +133,9 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
 #pragma unroll
     for (int e = 0; e < EPT; ++e) v[e] = (p0 + e < n) ? src[p0 + e] : -INFINITY;
   }
-  float lse = 0.f;                                        // log sum exp of the row (LSE && FINAL)
+  const bool fin = FINAL || n <= NW * 64 * EPT;           // uniform over the grid row
+  if (!FINAL && fin && c != 0) return;
+  float lse = 0.f;                                        // log sum exp of the row (LSE && fin)
   // ---- fast path: threshold from lane maxima, compaction, ranking
   {
     __shared__ float s_thr[NW];
@@ -176,7 +180,7 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
       float zmax = wave_max(wm);
       zmax = zmax == -INFINITY ? 0.f : zmax;                // empty chunk: every factor below is exp(-inf) = 0
       const float se = wave_add(lane < NW ? s_sum[lane] * expf(wm - zmax) : 0.f);
-      if (FINAL) lse = zmax + logf(se);
+      if (fin) lse = zmax + logf(se);
       else if (tid == 0) cand_ms[row * gridDim.x + c] = make_float2(zmax, se);
     }
     uint32_t flags = 0;
@@ -217,7 +221,7 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
         if (t < C) {
           val = s_cv[t];
           pos = s_cp[t];
-          if (FINAL) gid = ids ? ids[b * ids_stride + pos] : pos;   // in flight while the candidate is ranked
+          if (fin) gid = ids ? ids[b * ids_stride + pos] : pos;   // in flight while the candidate is ranked
           rank = 0;
 #pragma unroll 4
           for (int q = 0; q < C; ++q) {
@@ -226,7 +230,7 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
           }
         }
         if (rank < k) {
-          if (FINAL) {
+          if (fin) {
             o = row * k + rank;
             out_ids[o] = gid;
             if (out_vals) out_vals[o] = (LSE && val != -INFINITY) ? val - lse : val;
@@ -269,7 +273,7 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
   if (lane < k) {
     const bool none = (wval == -INFINITY);
     const int pos = none ? -1 : s_pos[wq];
-    if (FINAL) {
+    if (fin) {
       const int64_t o = row * k + lane;
       out_ids[o] = none ? -1 : (ids ? ids[b * ids_stride + pos] : pos);
       if (out_vals) out_vals[o] = (LSE && !none) ? wval - lse : wval;
@@ -286,9 +290,11 @@ template <bool LSE>
 __global__ __launch_bounds__(64) void topk_merge_kernel(const float* __restrict__ cand_val, const int32_t* __restrict__ cand_pos,
                                                         const float2* __restrict__ cand_ms, int nchunks,
                                                         const int32_t* __restrict__ ids, int64_t ids_stride, int M, int k,
-                                                        int32_t* __restrict__ out_ids, float* __restrict__ out_vals) {
+                                                        int32_t* __restrict__ out_ids, float* __restrict__ out_vals,
+                                                        const int32_t* __restrict__ n_dev, int n_fixed) {
   constexpr int EPT = 16;
   const int m = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
+  if ((n_dev ? n_dev[b] : n_fixed) <= kTopkChunk) return;   // the first chunk's workgroup has written the result
   const int64_t row = (int64_t)b * M + m;
   const int total = nchunks * k;
   const float* cv = cand_val + row * total;
@@ -362,10 +368,10 @@ static hipError_t launch_topk_t(const float* logits, int64_t ld, const int32_t* 
   int32_t* cp = reinterpret_cast<int32_t*>(ws + slots * 4);
   float2* ms = reinterpret_cast<float2*>(ws + slots * 8);
   topk_select_kernel<16, 16, false, LSE><<<dim3(nch, M, batch), 1024, 0, s>>>(logits, ld, ids, ids_stride, n_dev, n_fixed, M,
-                                                                            k, nullptr, nullptr, cv, cp, ms);
+                                                                            k, out_ids, out_vals, cv, cp, ms);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  topk_merge_kernel<LSE><<<rows, 64, 0, s>>>(cv, cp, ms, nch, ids, ids_stride, M, k, out_ids, out_vals);
+  topk_merge_kernel<LSE><<<rows, 64, 0, s>>>(cv, cp, ms, nch, ids, ids_stride, M, k, out_ids, out_vals, n_dev, n_fixed);
   return hipGetLastError();
 }
 

@@ -422,7 +422,7 @@ def test_device_side_feedback_loop():
         st.close()
 
 
-@pytest.mark.parametrize("window,n_ctx", [(64, 0), (64, 7), (3500, 3000), (12000, 9000), (40000, 33000)])
+@pytest.mark.parametrize("window,n_ctx", [(64, 0), (64, 7), (3500, 3000), (12000, 9000), (40000, 33000), (40000, 9000), (40000, 0)])
 def test_topk_logprob_against_oracle(window, n_ctx):
     """Selection with log-probabilities renormalised over the active set (Sec. 4.2): ids bit-exact against
     the oracle's selection; values within 1e-4 of the fp64 log-softmax (fp32 exp and a sum of at most 4e4

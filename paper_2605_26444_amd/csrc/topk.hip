@@ -355,8 +355,8 @@ static hipError_t launch_topk_t(const float* logits, int64_t ld, const int32_t* 
                                                             out_vals, nullptr, nullptr, nullptr);
     return hipGetLastError();
   }
-  if (cap <= 8192) {   // four wavefronts with 32 logits per lane beat sixteen with 16 (c3: 6.2 -> 5.5 us, c4: 8.2 -> 6.1 us)
-    topk_select_kernel<32, 4, true, LSE><<<rows, 256, 0, s>>>(logits, ld, ids, ids_stride, n_dev, n_fixed, M, k, out_ids,
+  if (cap <= 8192) {   // eight wavefronts beat sixteen (c3: 6.2 -> 5.0 us, c4: 8.2 -> 5.8 us) and four with 32 logits per lane (5.5, 6.1)
+    topk_select_kernel<16, 8, true, LSE><<<rows, 512, 0, s>>>(logits, ld, ids, ids_stride, n_dev, n_fixed, M, k, out_ids,
                                                             out_vals, nullptr, nullptr, nullptr);
     return hipGetLastError();
   }

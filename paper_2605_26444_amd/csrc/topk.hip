@@ -14,9 +14,12 @@
 // as gives each about 32 lanes of work (nwe <= NW; measured: spreading 150 runs over 16 wavefronts
 // loosens the bound below and costs 2-10 us on wide batches); if every such wavefront reports its
 // ceil(k/nwe)-th largest lane maximum, the smallest of those is a lower bound T on the row's k-th
-// largest value (at least k lanes hold something >= T), so only elements >= T can be winners.  They are compacted in position order into LDS (typically one or two dozen),
-// every thread ranks one candidate against all others, and rank r < k is output slot r.  If more
-// than kCandMax elements survive (heavy ties) the kernel falls back to the rounds.
+// largest value (at least k lanes hold something >= T), so only elements >= T can be winners.  They
+// are compacted in position order into LDS (typically one or two dozen; a DPP prefix sum over the
+// lanes and one over the wavefront totals), every thread ranks one candidate against all others while
+// its global id is being fetched, and rank r < k is output slot r.  If more than kCandMax elements
+// survive (heavy ties) the kernel falls back to the rounds.  (Handing out the LDS slots with one
+// atomic counter and breaking ties by position instead was measured slower than the prefix sums.)
 //
 // LSE variants (Sec. 4.2: the draft distribution is the softmax renormalised over the active set):
 // the same selection, with the values written as log-probabilities z - log(sum_i exp z_i), i over the

@@ -9,6 +9,8 @@
 // every entering id sets it (so an id that is evicted and re-appended in the same call ends up
 // correct whatever order the atomics landed in), and the union bitmap is compacted with popcounts
 // and a workgroup prefix scan.  Both bitmaps live in LDS during the kernel.
+// The paper's other description of the same state -- a first-in first-out queue of at most `window`
+// distinct ids -- is the second half of this file (vocab_fifo_kernel).
 #include "common.h"
 
 namespace nanospec {

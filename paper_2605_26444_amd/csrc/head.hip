@@ -67,6 +67,22 @@ __global__ __launch_bounds__(256) void head_generic_kernel(const uint16_t* __res
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// The dynamic-LDS limit of a kernel is a per-device attribute: remember per device whether it has been
+// raised (one flag array per kernel instantiation).  Returns true when the current device still needs it.
+struct PerDeviceOnce {
+  bool done[64] = {};
+  bool needed(int* dev) {
+    if (hipGetDevice(dev) != hipSuccess || *dev < 0 || *dev >= 64) {
+      *dev = -1;
+      return true;
+    }
+    return !done[*dev];
+  }
+  void mark(int dev) {
+    if (dev >= 0) done[dev] = true;
+  }
+};
+
 // sum over the four lanes of a quad, in every lane of it (DPP quad_perm: neighbours 1 apart, then 2 apart)
 __device__ __forceinline__ float quad_sum(float x) {
   x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xf, 0xf, true));   // quad_perm:[1,0,3,2]
@@ -352,15 +368,16 @@ static hipError_t run_quad(const uint16_t* W, const uint16_t* H, const int32_t* 
                            float* logits, hipStream_t s) {
   constexpr int ROWS = 4 * RT * NRG;
   constexpr int LDS = 4 * MT * KS * 1024 + 4 * NRG * (RT * MT * 16) * 4;
-  static bool configured = false;
-  if (!configured) {
+  static PerDeviceOnce once;
+  int dev;
+  if (once.needed(&dev)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_quad_kernel<NRG, RT, MT, KS, true>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (e == hipSuccess)
       e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_quad_kernel<NRG, RT, MT, KS, false>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (e != hipSuccess) return e;
-    configured = true;
+    once.mark(dev);
   }
   const int tiles = (cap_rows + ROWS - 1) / ROWS;
   const int seq_first = batch > 1 && tiles <= 65535;
@@ -513,12 +530,13 @@ __global__ __launch_bounds__(256) void head_splitk_reduce_kernel(const float* __
 
 template <int MT, bool LOOPK>
 static hipError_t tile64_configure() {
-  static bool configured = false;
-  if (!configured) {
+  static PerDeviceOnce once;
+  int dev;
+  if (once.needed(&dev)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_tile64_kernel<MT, LOOPK>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 16 * (1024 + 16));
     if (e != hipSuccess) return e;
-    configured = true;
+    once.mark(dev);
   }
   return hipSuccess;
 }

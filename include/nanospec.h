@@ -92,7 +92,8 @@ NANOSPEC_API nanospec_status nanospec_state_layout(int32_t V, int32_t d, int32_t
  * Limits: batch <= NANOSPEC_MAX_BATCH; min(window + topk_cap, V) <= 262144 (16 top-k chunks); the vocabulary
  * kernels keep three V-bit bitmaps in one workgroup's LDS, which bounds V at about 420 000.
  * Errors: EINVAL (null, a size < 1, d % 8 != 0, a limit above exceeded), ENOMEM, EHIP.
- * Synchronous (allocates).  The state starts empty: stream length 0, T empty, I empty. */
+ * Synchronous (allocates).  The state starts empty: stream length 0, T empty, I empty.  The state belongs to
+ * the device that is current here; every later call on it returns EINVAL if another device is current. */
 NANOSPEC_API nanospec_status nanospec_create(nanospec_state** out, int32_t V, int32_t d, int32_t batch,
                                 int32_t window, int32_t topk_cap, int32_t m_cap, int32_t k_cap);
 NANOSPEC_API nanospec_status nanospec_destroy(nanospec_state* st);

@@ -58,9 +58,16 @@ nanospec_status offsets_to_arg(const int32_t* h_off, int batch, Offsets* out, in
   return NANOSPEC_OK;
 }
 
+// The state's memory and its kernels belong to the device that was current at nanospec_create: a call made
+// with another device current would launch there on foreign pointers, so it is refused instead.
+bool wrong_device(const nanospec_state* st) {
+  int dev = -1;
+  return hipGetDevice(&dev) != hipSuccess || dev != st->device;
+}
+
 nanospec_status vocab_call(nanospec_state* st, const int32_t* d_new, const int32_t* h_noff, const int32_t* d_topk,
                            const int32_t* h_toff, bool is_init, void* stream) {
-  if (!st) return NANOSPEC_EINVAL;
+  if (!st || wrong_device(st)) return NANOSPEC_EINVAL;
   if (is_init && !h_noff) return NANOSPEC_EINVAL;
   Offsets noff, toff;
   bool any_new = false, any_t = false;
@@ -181,7 +188,8 @@ nanospec_status nanospec_vocab_update(nanospec_state* st, const int32_t* d_new_i
 
 nanospec_status nanospec_vocab_append_unique(nanospec_state* st, const int32_t* d_cand_ids, int32_t cand_per_seq,
                                              int64_t cand_stride, void* hip_stream) {
-  if (!st || cand_per_seq < 0 || (cand_per_seq > 0 && !d_cand_ids) || cand_stride < cand_per_seq) return NANOSPEC_EINVAL;
+  if (!st || cand_per_seq < 0 || (cand_per_seq > 0 && !d_cand_ids) || cand_stride < cand_per_seq || wrong_device(st))
+    return NANOSPEC_EINVAL;
   if (cand_per_seq > st->unique_cap) return NANOSPEC_ECAPACITY;
   hipError_t e = launch_vocab_append_unique(st, d_cand_ids, cand_per_seq, cand_stride, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;
@@ -198,7 +206,7 @@ nanospec_status nanospec_vocab_view(const nanospec_state* st, const int32_t** d_
 
 nanospec_status nanospec_sparse_head(nanospec_state* st, const void* d_W_bf16, const void* d_H_bf16, int32_t M,
                                      float* d_logits, void* hip_stream) {
-  if (!st || !d_W_bf16 || !d_H_bf16 || !d_logits || M < 1) return NANOSPEC_EINVAL;
+  if (!st || !d_W_bf16 || !d_H_bf16 || !d_logits || M < 1 || wrong_device(st)) return NANOSPEC_EINVAL;
   if (M > st->m_cap) return NANOSPEC_ECAPACITY;
   hipError_t e = launch_head(d_W_bf16, d_H_bf16, st->vp.ids, st->vp.n, 0, st->vp.cap, st->V, st->batch, M, st->d, st->vp.cap,
                              st->vp.cap, d_logits, st->partial, st->partial_bytes, static_cast<hipStream_t>(hip_stream));
@@ -207,7 +215,7 @@ nanospec_status nanospec_sparse_head(nanospec_state* st, const void* d_W_bf16, c
 
 nanospec_status nanospec_topk_remap(nanospec_state* st, const float* d_logits, int32_t M, int32_t k, int32_t* d_out_ids,
                                     float* d_out_vals, void* hip_stream) {
-  if (!st || !d_logits || !d_out_ids || M < 1 || k < 1) return NANOSPEC_EINVAL;
+  if (!st || !d_logits || !d_out_ids || M < 1 || k < 1 || wrong_device(st)) return NANOSPEC_EINVAL;
   if (M > st->m_cap || k > st->k_cap) return NANOSPEC_ECAPACITY;
   hipError_t e = launch_topk(d_logits, st->vp.cap, st->vp.ids, st->vp.cap, st->vp.n, 0, st->vp.cap, st->batch, M, k,
                              d_out_ids, d_out_vals, false, st->topk_ws, st->topk_ws_bytes,
@@ -217,7 +225,7 @@ nanospec_status nanospec_topk_remap(nanospec_state* st, const float* d_logits, i
 
 nanospec_status nanospec_topk_logprob_remap(nanospec_state* st, const float* d_logits, int32_t M, int32_t k,
                                             int32_t* d_out_ids, float* d_out_logprob, void* hip_stream) {
-  if (!st || !d_logits || !d_out_ids || !d_out_logprob || M < 1 || k < 1) return NANOSPEC_EINVAL;
+  if (!st || !d_logits || !d_out_ids || !d_out_logprob || M < 1 || k < 1 || wrong_device(st)) return NANOSPEC_EINVAL;
   if (M > st->m_cap || k > st->k_cap) return NANOSPEC_ECAPACITY;
   hipError_t e = launch_topk(d_logits, st->vp.cap, st->vp.ids, st->vp.cap, st->vp.n, 0, st->vp.cap, st->batch, M, k,
                              d_out_ids, d_out_logprob, true, st->topk_ws, st->topk_ws_bytes,
@@ -256,7 +264,7 @@ nanospec_status nanospec_calib_stream_read(const void* d_buf, int64_t bytes, voi
 }
 
 nanospec_status nanospec_calib_gather_read(nanospec_state* st, const void* d_W_bf16, void* d_sink, void* hip_stream) {
-  if (!st || !d_W_bf16 || !d_sink) return NANOSPEC_EINVAL;
+  if (!st || !d_W_bf16 || !d_sink || wrong_device(st)) return NANOSPEC_EINVAL;
   return launch_calib_gather(d_W_bf16, st->V, st->d, st->vp.ids, st->vp.n, st->vp.cap, d_sink,
                              static_cast<hipStream_t>(hip_stream)) == hipSuccess
              ? NANOSPEC_OK
@@ -264,7 +272,7 @@ nanospec_status nanospec_calib_gather_read(nanospec_state* st, const void* d_W_b
 }
 
 nanospec_status nanospec_last_device_error(nanospec_state* st, int32_t* flags, void* hip_stream) {
-  if (!st || !flags) return NANOSPEC_EINVAL;
+  if (!st || !flags || wrong_device(st)) return NANOSPEC_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   if (hipMemcpyAsync(st->h_err_pinned, st->vp.err, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return NANOSPEC_EHIP;
   if (hipMemsetAsync(st->vp.err, 0, 4, s) != hipSuccess) return NANOSPEC_EHIP;

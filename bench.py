@@ -330,13 +330,13 @@ def cpu_baseline(cfg, seqs, W_host, synth):
     for b in range(Bn):
         voc[b].init(seqs["ctx"][b], seqs["T0"][b])
 
-    def one(s):
+    def one(s, omp=True):
         Hs = synth.make_H(cfg, s % 16)
         for b in range(Bn):
             Ts = seqs["T_step"][s % len(seqs["T_step"])]
             voc[b].update(seqs["appends"][s % len(seqs["appends"])][b], Ts[b] if Ts is not None else None)
             act = voc[b].active()
-            z32, _ = oracle.head(W_host, Hs[b], ids=act, want64=False, omp=True)
+            z32, _ = oracle.head(W_host, Hs[b], ids=act, want64=False, omp=omp)
             for m in range(M):
                 oracle.topk(z32[m], act, k)
     t = time.time()
@@ -347,9 +347,21 @@ def cpu_baseline(cfg, seqs, W_host, synth):
     for s in range(1, 1 + n):
         one(s)
     el = time.time() - t
+    # the same steps on one thread (about 2 s of them), and the dense full-vocabulary head of one step once
+    n1 = int(min(max(2.0 / max(t1 * threads, 1e-3), 1), 200))
+    t = time.time()
+    for s in range(1 + n, 1 + n + n1):
+        one(s, omp=False)
+    el1 = time.time() - t
+    t = time.time()
+    Hs = synth.make_H(cfg, 0)
+    oracle.head(W_host, Hs[0], ids=None, want64=False, omp=True)
+    dense_s = (time.time() - t) * Bn
     return {"value": round(n / el, 3), "unit": "steps/s", "cores": threads, "kind": "oracle",
             "sample": f"{n} consecutive steps of the same workload (vocabulary rebuild + fp32 head + full-sort "
-                      f"top-k), OpenMP over active rows, {el:.1f} s"}
+                      f"top-k), OpenMP over active rows, {el:.1f} s",
+            "single_thread_steps_per_s": round(n1 / el1, 3), "single_thread_sample_steps": n1,
+            "dense_head_s_per_step": round(dense_s, 4)}
 
 
 if __name__ == "__main__":

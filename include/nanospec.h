@@ -10,6 +10,10 @@
  *   Eq. 2-3 candidate stream S, appended to at prefill and after every verification
  *   Eq. 4   I_t = Unique(Suffix(S, W_max))     active index set, recency eviction
  *   Alg. 1  SelectDraftTokens(z', I)           top-k over z' mapped back to global ids
+ *   Sec 3.3 / appendix                         the same state read as a first-in first-out queue of
+ *                                              distinct ids (nanospec_set_stream_policy)
+ *   Sec 4.2 softmax over the active set only   log-probabilities with the selection
+ *                                              (nanospec_topk_logprob_remap)
  *
  * Conventions
  *   - Token ids are 0-based int32 in [0, V).

@@ -677,3 +677,97 @@ def test_limits_largest_batch():
             ei, _ = oracle.topk(g[b, m, :len(exp)], exp, k)
             assert np.array_equal(gi[b, m], ei), (b, m)
     st.close()
+
+
+# ---- randomised sweeps (fixed seeds): many small states / shapes that no hand-written case names
+
+def test_randomised_vocabulary_calls():
+    """200 random states: both policies, V 200..200k, window 1..5000, mixed update / T replacement / append_unique,
+    appends up to twice the window plus a chunk; the active set is compared after every call."""
+    for seed in range(200):
+        rng = np.random.default_rng(1000 + seed)
+        V = int(rng.choice([200, 5000, 70000, 140000, 200000]))
+        W = int(rng.choice([1, 3, 37, 300, 1024, 2500, 5000]))
+        Bn = int(rng.choice([1, 2, 5, 9]))
+        tcap = int(rng.choice([0, 5, 64]))
+        pol = int(rng.integers(0, 2))
+        vals = int(rng.choice([min(V, 50), min(V, 400), V]))
+        st = B.State(V, 64, Bn, W, tcap, 4, 8)
+        B.nanospec_set_stream_policy(st.h, pol)
+        orc = [oracle.FifoVocab(V, W) if pol else oracle.Vocab(V, W) for _ in range(Bn)]
+        ctx = [rng.integers(0, vals, size=int(rng.integers(0, 3 * W + 50))).astype(np.int32) for _ in range(Bn)]
+        T = [rng.integers(0, V, size=int(rng.integers(0, tcap + 1))).astype(np.int32) for _ in range(Bn)]
+        f, off = csr(ctx)
+        tf, toff = csr(T)
+        B.nanospec_vocab_init(st.h, dev_ids(f), off, dev_ids(tf), toff)
+        for b in range(Bn):
+            orc[b].init(ctx[b], T[b])
+        for step in range(12):
+            kind = int(rng.integers(0, 4))
+            if kind == 3:
+                per = int(rng.integers(1, 40))
+                cand = rng.integers(-1, vals, size=(Bn, per)).astype(np.int32)
+                B.nanospec_vocab_append_unique(st.h, dev(cand), per, per)
+                for b in range(Bn):
+                    orc[b].append_unique(cand[b])
+            else:
+                big = step % 9 == 0
+                new = [rng.integers(0, vals, size=int(rng.integers(0, (2 * W + 1100) if big else 9))).astype(np.int32)
+                       for _ in range(Bn)]
+                f, off = csr(new)
+                if kind == 2:
+                    T = [rng.integers(0, V, size=int(rng.integers(0, tcap + 1))).astype(np.int32) for _ in range(Bn)]
+                    tf, toff = csr(T)
+                    B.nanospec_vocab_update(st.h, dev_ids(f), off, dev_ids(tf), toff)
+                else:
+                    B.nanospec_vocab_update(st.h, dev_ids(f), off)
+                for b in range(Bn):
+                    orc[b].update(new[b], T[b] if kind == 2 else None)
+            act = st.read_active()
+            for b in range(Bn):
+                assert np.array_equal(act[b], orc[b].active()), (seed, step, b, V, W, pol)
+        st.close()
+
+
+def test_randomised_head_shapes():
+    """40 random (d, M, rows, sequences, k): logits within tolerance, plain and log-probability selection exact on
+    the GPU's own logits."""
+    for case in range(40):
+        rng = np.random.default_rng(5000 + case)
+        d = int(rng.choice([8, 64, 520, 1032, 2048, 3592, 4096, 4104, 8192]))
+        M = int(rng.choice([1, 2, 4, 5, 8, 9, 12, 16, 17, 32, 33, 64, 65, 70]))
+        batch = int(rng.choice([1, 1, 1, 2, 3]))
+        nmax = int(rng.choice([5, 70, 700, 3000]))
+        V = max(nmax + 10, int(rng.choice([1000, 20000])))
+        k = int(rng.choice([1, 5, 10, 64]))
+        W = synth.normal_bf16(7000 + case, 0, (V, d), 0.02, threads=4)
+        H = synth.normal_bf16(7000 + case, 1, (batch, M, d), 1.0, threads=1)
+        st = B.State(V, d, batch, nmax, 0, M, k)
+        ctx = [rng.choice(V, size=int(rng.integers(0, nmax + 1)), replace=False).astype(np.int32) for _ in range(batch)]
+        f, off = csr(ctx)
+        B.nanospec_vocab_init(st.h, dev_ids(f), off, None, np.zeros(batch + 1, np.int32))
+        logits = torch.full((batch, M, st.capacity), float("nan"), dtype=torch.float32, device="cuda")
+        oi = torch.empty((batch, M, k), dtype=torch.int32, device="cuda")
+        ov = torch.empty((batch, M, k), dtype=torch.float32, device="cuda")
+        li, lv = torch.empty_like(oi), torch.empty_like(ov)
+        B.nanospec_sparse_head(st.h, dev_bf16(W), dev_bf16(H), M, logits)
+        B.nanospec_topk_remap(st.h, logits, M, k, oi, ov)
+        B.nanospec_topk_logprob_remap(st.h, logits, M, k, li, lv)
+        torch.cuda.synchronize()
+        act, g = st.read_active(), logits.cpu().numpy()
+        gi, gv, gli, glv = oi.cpu().numpy(), ov.cpu().numpy(), li.cpu().numpy(), lv.cpu().numpy()
+        for b in range(batch):
+            a = act[b]
+            n = len(a)
+            assert np.array_equal(a, np.sort(ctx[b])), case
+            if n:
+                o32, o64 = oracle.head(W, H[b], ids=a, omp=True)
+                assert_logits_close(g[b][:, :n], o64, o32, what=f"case {case} (d={d} M={M} n={n}) seq {b}")
+            for m in range(M):
+                ei, ev = oracle.topk(g[b, m, :n], a, k)
+                assert np.array_equal(gi[b, m], ei) and np.array_equal(gv[b, m], ev), (case, b, m)
+                _, elp = oracle.topk_logprob(g[b, m, :n], a, k)
+                fin = np.isfinite(elp)
+                assert np.array_equal(gli[b, m], ei), (case, b, m)
+                assert np.all(np.abs(glv[b, m][fin].astype(np.float64) - elp[fin]) <= 1e-4), (case, b, m)
+        st.close()

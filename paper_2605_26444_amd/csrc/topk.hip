@@ -10,16 +10,18 @@
 // them.  Rows longer than one workgroup's reach are cut into chunks whose winners a second kernel
 // merges the same way.  Values of -inf mark "nothing left" (logits are finite by contract).
 //
-// Fast path in front of the rounds: the valid runs of a row are split evenly over as many wavefronts
-// as gives each about 32 lanes of work (nwe <= NW; measured: spreading 150 runs over 16 wavefronts
-// loosens the bound below and costs 2-10 us on wide batches); if every such wavefront reports its
-// ceil(k/nwe)-th largest lane maximum, the smallest of those is a lower bound T on the row's k-th
-// largest value (at least k lanes hold something >= T), so only elements >= T can be winners.  They
-// are compacted in position order into LDS (typically one or two dozen; a DPP prefix sum over the
-// lanes and one over the wavefront totals), every thread ranks one candidate against all others while
-// its global id is being fetched, and rank r < k is output slot r.  If more than kCandMax elements
-// survive (heavy ties) the kernel falls back to the rounds.  (Handing out the LDS slots with one
-// atomic counter and breaking ties by position instead was measured slower than the prefix sums.)
+// Fast path in front of the rounds: lane l of wavefront w always holds positions (64w + l)*EPT ..., whatever
+// the row's length n, so the logits are requested before n has arrived and masked afterwards.  The nwe
+// wavefronts that are at least half full (or the first one) each report their ceil(k/nwe)-th largest lane
+// maximum; the smallest report is a lower bound T on the row's k-th largest value (at least k lanes hold
+// something >= T), so only elements >= T can be winners.  They are compacted in position order into LDS
+// (typically one or two dozen; a DPP prefix sum over the lanes and one over the wavefront totals), every
+// thread ranks one candidate against all others while its global id is being fetched, and rank r < k is
+// output slot r.  If more than kCandMax elements survive (heavy ties) the kernel falls back to the rounds.
+// Measured and not kept: handing out the LDS slots with one atomic counter and breaking ties by position;
+// splitting the valid runs evenly over the wavefronts (the layout then depends on n: c2 4.2 against
+// 4.1 us, c3 5.0 against 4.6); fetching every lane's 16 ids beside its logits so that the winners' ids
+// need no second round trip (4.3-4.4 us on c2).
 //
 // LSE variants (Sec. 4.2: the draft distribution is the softmax renormalised over the active set):
 // the same selection, with the values written as log-probabilities z - log(sum_i exp z_i), i over the
@@ -68,6 +70,20 @@ __device__ __forceinline__ float wave_add(float x) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
 }
 
+// v[e] for a lane-varying e in [0, 16): a select tree (4 compares + 15 selects) instead of 16 predicated
+// moves.  The elements arrive as sixteen scalars: selects between array elements get folded into a
+// lane-varying array index, and that puts the whole array into scratch memory.
+__device__ __forceinline__ float sel(bool c, float a, float b) { return c ? a : b; }
+__device__ __forceinline__ float pick16(float v0, float v1, float v2, float v3, float v4, float v5, float v6, float v7,
+                                        float v8, float v9, float v10, float v11, float v12, float v13, float v14,
+                                        float v15, int e) {
+  const bool b0 = e & 1, b1 = e & 2, b2 = e & 4, b3 = e & 8;
+  const float a0 = sel(b0, v1, v0), a1 = sel(b0, v3, v2), a2 = sel(b0, v5, v4), a3 = sel(b0, v7, v6);
+  const float a4 = sel(b0, v9, v8), a5 = sel(b0, v11, v10), a6 = sel(b0, v13, v12), a7 = sel(b0, v15, v14);
+  const float c0 = sel(b1, a1, a0), c1 = sel(b1, a3, a2), c2 = sel(b1, a5, a4), c3 = sel(b1, a7, a6);
+  return sel(b3, sel(b2, c3, c2), sel(b2, c1, c0));
+}
+
 // k rounds over the EPT values each lane holds (position = lane*EPT + register index).
 // emit(r, value, position) is called by every lane with wave-uniform arguments; value == -inf
 // means that fewer than r+1 elements exist.
@@ -95,6 +111,8 @@ __device__ __forceinline__ void wave_select(float (&v)[EPT], int k, int lane, Em
 // CH = NW*64*EPT.  FINAL: write global ids / values; else (value, position) for the merge kernel --
 // unless the whole row fits the first chunk (n <= CH, known only on the device): then chunk 0 writes the
 // final result itself, the other chunks leave at once and the merge kernel has nothing to do.
+constexpr int kLaneCand = 4;   // candidates per lane the owner path keeps in registers
+
 template <int EPT, int NW, bool FINAL, bool LSE>
 __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __restrict__ logits, int64_t ld,
                                                              const int32_t* __restrict__ ids, int64_t ids_stride,
@@ -107,35 +125,37 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
   __shared__ int s_pos[NW * kMaxK];
   const int c = blockIdx.x, m = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n = n_dev ? n_dev[b] : n_fixed;
   const int64_t row = (int64_t)b * M + m;
   const float* src = logits + row * ld;
-  // The valid runs of this chunk are split evenly over the wavefronts (contiguous, in order): every
-  // wavefront sees the same share of the row and position order is still (wavefront, lane, register).
+  // Position order is (wavefront, lane, register) and does not depend on the row's length, so the logits
+  // are requested before the length has arrived: bounded by the row stride, masked by n afterwards.
   const int cbase = c * (NW * 64 * EPT);
-  const int left = n - cbase;
-  const int runs = left > 0 ? (left + EPT - 1) / EPT : 0;
-  int nwe = (runs + 31) / 32;                              // wavefronts that take part
-  nwe = nwe < 1 ? 1 : (nwe > NW ? NW : nwe);
-  int per_wave = (runs + nwe - 1) / nwe;
-  per_wave = per_wave > 64 ? 64 : per_wave;
-  const int p0 = lane < per_wave ? cbase + (wave * per_wave + lane) * EPT : INT_MAX - EPT;   // first position of this lane's run
-
+  const int p0 = cbase + (wave * 64 + lane) * EPT;         // first position of this lane's run
   float v[EPT];
   if ((ld & 3) == 0) {
 #pragma unroll
     for (int e = 0; e < EPT; e += 4) {
       float4 x = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-      if (p0 + e < n) x = *reinterpret_cast<const float4*>(src + p0 + e);   // row stride is a multiple of 4
-      v[e] = (p0 + e < n) ? x.x : -INFINITY;
-      v[e + 1] = (p0 + e + 1 < n) ? x.y : -INFINITY;
-      v[e + 2] = (p0 + e + 2 < n) ? x.z : -INFINITY;
-      v[e + 3] = (p0 + e + 3 < n) ? x.w : -INFINITY;
+      if (p0 + e < ld) x = *reinterpret_cast<const float4*>(src + p0 + e);   // row stride is a multiple of 4
+      v[e] = x.x;
+      v[e + 1] = x.y;
+      v[e + 2] = x.z;
+      v[e + 3] = x.w;
     }
   } else {
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) v[e] = (p0 + e < n) ? src[p0 + e] : -INFINITY;
+    for (int e = 0; e < EPT; ++e) v[e] = (p0 + e < ld) ? src[p0 + e] : -INFINITY;
   }
+  const int n = n_dev ? n_dev[b] : n_fixed;
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) v[e] = (p0 + e < n) ? v[e] : -INFINITY;
+  // Wavefronts that are at least half full (or the first one) vote on the threshold; nwa hold anything at all.
+  const int left = n - cbase;
+  const int runs = left > 0 ? (left + EPT - 1) / EPT : 0;
+  int nwe = (runs + 32) / 64;
+  nwe = nwe < 1 ? 1 : (nwe > NW ? NW : nwe);
+  int nwa = (runs + 63) / 64;
+  nwa = nwa > NW ? NW : nwa;
   const bool fin = FINAL || n <= NW * 64 * EPT;           // uniform over the grid row
   if (!FINAL && fin && c != 0) return;
   float lse = 0.f;                                        // log sum exp of the row (LSE && fin)
@@ -145,7 +165,7 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
     __shared__ float s_wmax[NW];
     __shared__ float s_sum[NW];
     __shared__ int s_cnt[NW];
-    __shared__ float s_cv[kCandMax];
+    __shared__ __attribute__((aligned(16))) float s_cv[kCandMax + 4];
     __shared__ int s_cp[kCandMax];
     float ml = v[0];
 #pragma unroll
@@ -155,7 +175,7 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
     float wmax = -INFINITY, wsum = 0.f;
     for (int r = 0; r < rounds; ++r) {
       thr = wave_max(x);
-      if (LSE && r == 0 && wave < nwe) {                    // the first round's result is the wavefront's maximum;
+      if (LSE && r == 0 && wave < nwa) {                    // the first round's result is the wavefront's maximum;
         wmax = thr;                                         // its exp-sum is independent work between the rounds
         const float ref = wmax == -INFINITY ? 0.f : wmax;   // nothing valid here: every term is exp(-inf) = 0
         float se = 0.f;
@@ -197,14 +217,85 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
     incl += __builtin_amdgcn_update_dpp(0, incl, 0x118, 0xf, 0xf, false);   // row_shr:8
     incl += __builtin_amdgcn_update_dpp(0, incl, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
     incl += __builtin_amdgcn_update_dpp(0, incl, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
-    if (lane == 63) s_cnt[wave] = incl;
+    const int crowded = __ballot(mine > kLaneCand) != 0ull ? 1 << 20 : 0;   // some lane holds more than the owner path keeps
+    if (lane == 63) s_cnt[wave] = incl | crowded;
     __syncthreads();
-    int off = incl - mine, C = 0;
+    int off = incl - mine, C = 0, any_crowded = 0;
 #pragma unroll
     for (int ww = 0; ww < NW; ++ww) {
-      const int t = s_cnt[ww];
+      const int t = s_cnt[ww] & 0xfffff;
+      any_crowded |= s_cnt[ww] >> 20;
       if (ww < wave) off += t;
       C += t;
+    }
+    if (EPT == 16 && C <= kCandMax && !any_crowded) {     // uniform over the workgroup
+      // Owner path: the lane that holds a candidate asks for its global id at once (up to kLaneCand per
+      // lane), the values alone meet in LDS, every thread ranks one of them, and the owner -- whose id has
+      // arrived meanwhile -- writes the output slot its candidate's rank names.
+      float cval[kLaneCand];
+      int cgid[kLaneCand];
+      uint32_t f = flags;
+#pragma unroll
+      for (int j = 0; j < kLaneCand; ++j) {
+        cval[j] = 0.f;
+        cgid[j] = 0;
+        if (__ballot(f != 0u) != 0ull) {                    // some lane of this wavefront has a j-th candidate
+          const int e = f ? __ffs(f) - 1 : 0;
+          cval[j] = pick16(v[0], v[1], v[2], v[3], v[4], v[5], v[6], v[7], v[8], v[9], v[10], v[11], v[12], v[13], v[14],
+                           v[15], e);
+          cgid[j] = p0 + e;
+          if (f) {
+            if (fin && ids) cgid[j] = ids[b * ids_stride + p0 + e];
+            s_cv[off + j] = cval[j];
+          }
+          f &= f - 1u;
+        }
+      }
+      if (tid < 4) s_cv[C + tid] = __builtin_nanf("");     // pads the last group of four; compares false with everything
+      if (tid < C) s_cp[tid] = 0;                           // rank of candidate tid, accumulated below
+      __syncthreads();
+      // Work item (t, g): candidate t against the g-th group of four candidates; t is the fast index
+      // (padded to a power of two), so a few dozen candidates are ranked in one sweep of the workgroup.
+      const int lg = C <= 1 ? 0 : 32 - __clz(C - 1);
+      const int items = ((C + 3) >> 2) << lg;
+      for (int w = tid; w < items; w += 64 * NW) {
+        const int t = w & ((1 << lg) - 1), q = (w >> lg) * 4;
+        if (t < C) {
+          const float val = s_cv[t];
+          const float4 o = *reinterpret_cast<const float4*>(&s_cv[q]);
+          int r = (o.x > val || (o.x == val && q < t)) ? 1 : 0;         // list order is position order
+          r += (o.y > val || (o.y == val && q + 1 < t)) ? 1 : 0;
+          r += (o.z > val || (o.z == val && q + 2 < t)) ? 1 : 0;
+          r += (o.w > val || (o.w == val && q + 3 < t)) ? 1 : 0;
+          if (r) atomicAdd(&s_cp[t], r);
+        }
+      }
+      if (tid >= C && tid < k) {                            // padding slots when fewer than k exist
+        if (fin) {
+          out_ids[row * k + tid] = -1;
+          if (out_vals) out_vals[row * k + tid] = -INFINITY;
+        } else {
+          cand_val[(row * gridDim.x + c) * k + tid] = -INFINITY;
+          cand_pos[(row * gridDim.x + c) * k + tid] = -1;
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < kLaneCand; ++j) {
+        const int rank = j < mine ? s_cp[off + j] : k;
+        if (rank < k) {
+          if (fin) {
+            const int64_t o = row * k + rank;
+            out_ids[o] = cgid[j];
+            if (out_vals) out_vals[o] = (LSE && cval[j] != -INFINITY) ? cval[j] - lse : cval[j];
+          } else {
+            const int64_t o = (row * gridDim.x + c) * k + rank;
+            cand_val[o] = cval[j];
+            cand_pos[o] = cgid[j];
+          }
+        }
+      }
+      return;
     }
     if (C <= kCandMax) {                                  // uniform over the workgroup
 #pragma unroll
@@ -248,7 +339,7 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
     }
   }
   // ---- general path: k rounds per wavefront, then over the wavefronts' winners
-  const int wbase = cbase + wave * per_wave * EPT;
+  const int wbase = cbase + wave * 64 * EPT;
   wave_select<EPT>(v, k, lane, [&](int r, float val, int pos) {
     if (lane == 0) {
       s_val[wave * k + r] = val;

@@ -227,6 +227,52 @@ def test_topk_all_equal_and_signed_zero(V):
     st.close()
 
 
+@pytest.mark.parametrize("V,n_ctx", [(4096, 3017), (7000, 6500), (12000, 11111), (40000, 33000)])   # one per selection kernel + chunked
+@pytest.mark.parametrize("k", [1, 10, 64])
+def test_topk_winner_placement(V, n_ctx, k):
+    """Winners crowded into one lane's run of 16 positions, exactly four / five of them in one run, a few
+    dozen equal maxima spread over the row, winners only in the ragged last run, and a descending ramp:
+    every route through the selection kernel gives the oracle's ids and values, with and without
+    log-probabilities."""
+    d, M = 8, 8
+    st = B.State(V, d, 1, V, 0, M, 64)
+    rng = np.random.default_rng(V + k)
+    ctx = rng.choice(V, size=n_ctx, replace=False).astype(np.int32)
+    B.nanospec_vocab_init(st.h, dev_ids(ctx), [0, n_ctx], None, [0, 0])
+    act = st.read_active()[0]
+    n, cap = len(act), st.capacity
+    z = np.full((1, M, cap), np.nan, np.float32)
+    base = rng.normal(size=(M, n)).astype(np.float32)
+    at = 16 * (n // 32)                                           # start of a run somewhere in the middle
+    base[0, at:at + 16] += 20.0 + rng.normal(size=16)             # 16 winners in one lane
+    base[1, at + 3:at + 7] += 20.0                                # exactly four in one lane
+    base[2, at + 3:at + 8] += 20.0                                # five in one lane
+    base[3, rng.choice(n, size=40, replace=False)] = 9.0          # 40 equal maxima: ranked by position
+    base[4, n - (n % 16 or 16):] += 30.0                          # winners in the ragged tail
+    base[5] = np.linspace(5.0, -5.0, n, dtype=np.float32)         # descending ramp: the first k positions
+    base[6] = np.linspace(-5.0, 5.0, n, dtype=np.float32)         # ascending ramp: the last k positions
+    base[7, :] = np.float32(0.5)
+    base[7, rng.choice(n, size=min(n, 300), replace=False)] = 0.75   # 300 equal maxima: more than the candidate list holds
+    z[0, :, :n] = base
+    lg = dev(z)
+    oi = torch.empty((1, M, k), dtype=torch.int32, device="cuda")
+    ov = torch.empty((1, M, k), dtype=torch.float32, device="cuda")
+    ol = torch.empty((1, M, k), dtype=torch.float32, device="cuda")
+    oi2 = torch.empty_like(oi)
+    B.nanospec_topk_remap(st.h, lg, M, k, oi, ov)
+    B.nanospec_topk_logprob_remap(st.h, lg, M, k, oi2, ol)
+    torch.cuda.synchronize()
+    gi, gv, gl = oi.cpu().numpy()[0], ov.cpu().numpy()[0], ol.cpu().numpy()[0]
+    assert torch.equal(oi, oi2)
+    for m in range(M):
+        ei, ev = oracle.topk(z[0, m, :n], act, k)
+        assert np.array_equal(gi[m], ei), f"row {m}"
+        assert np.array_equal(gv[m], ev), f"row {m}"
+        _, elp = oracle.topk_logprob(z[0, m, :n], act, k)
+        assert np.all(np.abs(gl[m].astype(np.float64) - elp) <= 1e-4), f"row {m}"
+    st.close()
+
+
 def test_result_independent_of_position_and_run():
     """the logit of a (W row, H row) pair does not depend on where the row sits in the active list,
     and two runs give identical bits."""

@@ -11,6 +11,8 @@
 // and a workgroup prefix scan.  Both bitmaps live in LDS during the kernel.
 // The paper's other description of the same state -- a first-in first-out queue of at most `window`
 // distinct ids -- is the second half of this file (vocab_fifo_kernel).
+#include <limits.h>
+
 #include "common.h"
 
 namespace nanospec {
@@ -213,6 +215,199 @@ __device__ __forceinline__ void load_bitmaps(const VocabPtrs& p, int b, uint32_t
   }
 }
 
+// A short append (at most kIncMax ids, T untouched) changes the active list in at most 2*kIncMax places,
+// so the list is patched instead of rebuilt.  The bitmaps stay in HBM.  The first wavefront does all of
+// the bookkeeping: lanes 0..15 take the ring slots that leave the window, lanes 16..31 the appended ids;
+// lanes that hold the same id are found by comparing (a handful of readlanes), the first of them reads the
+// id's counter, adds the net change and writes it back -- no atomics, nobody else touches this sequence --
+// and a counter that becomes or stops being zero flips the window bit.  Such an id leaves / enters the
+// active set unless T holds it.  Every thread then moves its four list entries by (entered ids below) -
+// (left ids below); an entered id is written by the thread that holds its predecessor.  The result is
+// the list a full compaction would give; when nothing entered or left -- the usual case for text that
+// repeats itself -- the list is not touched at all.
+// Returns false, before anything has been changed, when the list is too close to its capacity (the
+// caller then takes the general path); the decision is uniform over the workgroup.
+constexpr int kIncMax = 16;
+constexpr int kIncPass = 4 * kVocabThreads;   // list entries per pass
+
+__device__ __forceinline__ bool vocab_apply_incremental(const VocabPtrs& p, int b, const int32_t* src, int a, int* sh) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int V = p.V, W = p.window, cap = p.cap;
+  int32_t* ids = p.ids + (size_t)b * cap;
+  uint32_t* gw = p.wbit + (size_t)b * p.nwords;
+  const uint32_t* gt = p.tbit + (size_t)b * p.nwords;
+  uint32_t* cnt = p.cnt + (size_t)b * V;
+  int32_t* ring = p.ring + (size_t)b * W;
+  // everything that does not depend on the state's scalars is requested first
+  const int n_old = p.n[b], pos = p.pos[b], fill = p.fill[b];
+  const bool ap = tid >= kIncMax && tid < kIncMax + a;        // this thread appends src[tid - kIncMax]
+  int v = -1;
+  if (ap) v = src[tid - kIncMax];
+  int4 q0 = make_int4(INT_MAX, INT_MAX, INT_MAX, INT_MAX);
+  int q0n = INT_MAX;
+  if (4 * tid < cap) q0 = *reinterpret_cast<const int4*>(ids + 4 * tid);   // cap is a multiple of 4
+  if (4 * tid + 4 < cap) q0n = ids[4 * tid + 4];
+  if (n_old + a > cap) return false;
+  auto mask_pass = [&](int pass, const int4& q, int nx, int (&x)[5]) {
+    const int j0 = pass * kIncPass + 4 * tid;
+    x[0] = j0 < n_old ? q.x : INT_MAX;
+    x[1] = j0 + 1 < n_old ? q.y : INT_MAX;
+    x[2] = j0 + 2 < n_old ? q.z : INT_MAX;
+    x[3] = j0 + 3 < n_old ? q.w : INT_MAX;
+    x[4] = j0 + 4 < n_old ? nx : INT_MAX;
+  };
+  int xs[5];
+  mask_pass(0, q0, q0n, xs);
+
+  int n_evict = fill + a - W;                // a <= W here
+  if (n_evict < 0) n_evict = 0;
+  int oldest = pos - fill;
+  if (oldest < 0) oldest += W;
+  int* sR = sh;                              // ids that left the active set
+  int* sA = sh + 2 * kIncMax;                // ids that entered it
+  int* sO = sh + 4 * kIncMax;                // per entered id: (entered ids below it) - (left ids below it)
+  int* sN = sh + 6 * kIncMax;                // counts
+  int bad = 0;
+
+  if (tid < 64) {
+    int id = -1;
+    if (ap) {
+      if ((unsigned)v < (unsigned)V) id = v;
+      else bad = 1;
+    } else if (lane < n_evict) {
+      int slot = oldest + lane;
+      if (slot >= W) slot -= W;
+      id = ring[slot];
+    }
+    const bool valid = id >= 0;
+    uint32_t tw = 0u, oldc = 0u;
+    if (valid) {
+      tw = gt[id >> 5];
+      oldc = cnt[id];
+    }
+    // net change of this lane's id over all lanes, and whether an earlier lane holds the same id
+    int total = 0;
+    bool first = true;
+    for (int j = 0; j < n_evict; ++j) {
+      const bool same = valid && __builtin_amdgcn_readlane(id, j) == id;
+      total -= same ? 1 : 0;
+      first = first && !(same && j < lane);
+    }
+    for (int j = kIncMax; j < kIncMax + a; ++j) {
+      const bool same = valid && __builtin_amdgcn_readlane(id, j) == id;
+      total += same ? 1 : 0;
+      first = first && !(same && j < lane);
+    }
+    if (ap) {
+      int slot = pos + (lane - kIncMax);
+      if (slot >= W) slot -= W;
+      ring[slot] = id;                         // the leaving entries are in registers by now; -1 for an id out of range
+    }
+    const bool lead = valid && first;
+    const uint32_t newc = oldc + (uint32_t)total;
+    const uint32_t bit = 1u << (id & 31);
+    if (lead && total != 0) cnt[id] = newc;
+    const bool left = lead && oldc != 0u && newc == 0u, entered = lead && oldc == 0u && newc != 0u;
+    if (left) atomicAnd(&gw[id >> 5], ~bit);   // another lane may own a different bit of the same word
+    if (entered) atomicOr(&gw[id >> 5], bit);
+    const int r = (left && !(tw & bit)) ? id : INT_MAX;
+    const int av = (entered && !(tw & bit)) ? id : INT_MAX;
+    const unsigned long long mr = __ballot(r != INT_MAX), ma = __ballot(av != INT_MAX);
+    const unsigned long long lower = (1ull << lane) - 1ull;
+    if (r != INT_MAX) sR[__popcll(mr & lower)] = r;
+    int o = 0;
+    for (unsigned long long m = mr; m; m &= m - 1ull) o -= __builtin_amdgcn_readlane(r, __ffsll((long long)m) - 1) < av ? 1 : 0;
+    for (unsigned long long m = ma; m; m &= m - 1ull) o += __builtin_amdgcn_readlane(av, __ffsll((long long)m) - 1) < av ? 1 : 0;
+    if (av != INT_MAX) {
+      const int slot = __popcll(ma & lower);
+      sA[slot] = av;
+      sO[slot] = o;
+    }
+    if (lane == 0) {
+      sN[0] = __popcll(mr);
+      sN[1] = __popcll(ma);
+    }
+  }
+  __syncthreads();
+  const int nR = sN[0], nA = sN[1];
+  if (nR + nA) {
+    int lowest = INT_MAX;
+    for (int q = 0; q < nR; ++q) lowest = min(lowest, sR[q]);
+    for (int q = 0; q < nA; ++q) lowest = min(lowest, sA[q]);
+    const int passes = n_old / kIncPass + 1;
+    for (int pass = 0; pass < passes; ++pass) {
+      int4 qn = make_int4(INT_MAX, INT_MAX, INT_MAX, INT_MAX);
+      int qnn = INT_MAX;
+      if (pass + 1 < passes) {                 // the next pass is read before this one is written
+        const int j1 = (pass + 1) * kIncPass + 4 * tid;
+        if (j1 < cap) qn = *reinterpret_cast<const int4*>(ids + j1);
+        if (j1 + 4 < cap) qnn = ids[j1 + 4];
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+      }
+      const int j0 = pass * kIncPass + 4 * tid;
+      const bool head = j0 == 0;
+      if (xs[4] > lowest || head) {            // entries below every change stay where they are
+        // changes below the thread's first entry shift all four alike; a change inside its span (rare: at
+        // most one thread per change) is worked out entry by entry on top of that
+        int m0 = 0, inside = 0;
+        for (int q = 0; q < nR; ++q) {
+          const int x = __builtin_amdgcn_readfirstlane(sR[q]);
+          const int lt0 = x < xs[0] ? 1 : 0;
+          m0 -= lt0;
+          inside += (x < xs[4] ? 1 : 0) - lt0;
+        }
+        for (int q = 0; q < nA; ++q) {
+          const int x = __builtin_amdgcn_readfirstlane(sA[q]);
+          const int lt0 = x < xs[0] ? 1 : 0;
+          m0 += lt0;
+          inside += (x < xs[4] ? 1 : 0) - lt0;
+        }
+        int mv[4] = {m0, m0, m0, m0};
+        bool dead[4] = {false, false, false, false};
+        if (inside != 0 || (head && m0 != 0)) {
+          for (int q = 0; q < nR; ++q) {
+            const int x = __builtin_amdgcn_readfirstlane(sR[q]);
+            if (x >= xs[0] && x < xs[4]) {
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                mv[i] -= x < xs[i] ? 1 : 0;
+                dead[i] = dead[i] || x == xs[i];
+              }
+            }
+          }
+          for (int q = 0; q < nA; ++q) {
+            const int x = __builtin_amdgcn_readfirstlane(sA[q]);
+            const int below = __builtin_amdgcn_readfirstlane(sO[q]);
+            if (x >= xs[0] && x < xs[4]) {
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                mv[i] += x < xs[i] ? 1 : 0;
+                if (xs[i] < x && x < xs[i + 1]) ids[j0 + i + 1 + below] = x;
+              }
+            }
+            if (head && x < xs[0]) ids[below] = x;     // in front of the whole list
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (xs[i] != INT_MAX && !dead[i] && mv[i] != 0) ids[j0 + i + mv[i]] = xs[i];
+      }
+      mask_pass(pass + 1, qn, qnn, xs);
+    }
+  }
+  if (tid == 0) {
+    p.n[b] = n_old + nA - nR;
+    int np = pos + a;
+    if (np >= W) np -= W;
+    p.pos[b] = np;
+    const int nf = fill + a;
+    p.fill[b] = nf < W ? nf : W;
+  }
+  if (bad) atomicOr(p.err, (int)NANOSPEC_DEV_BAD_ID);
+  return true;
+}
+
 __global__ __launch_bounds__(kVocabThreads) void vocab_apply_kernel(VocabPtrs p, const int32_t* __restrict__ new_ids,
                                                                     Offsets noff, const int32_t* __restrict__ topk,
                                                                     Offsets toff, int replace_T) {
@@ -221,9 +416,12 @@ __global__ __launch_bounds__(kVocabThreads) void vocab_apply_kernel(VocabPtrs p,
   uint32_t* wb = lds;
   uint32_t* tb = lds + p.nwords;
   int* sc = reinterpret_cast<int*>(tb + p.nwords);   // 16 wave totals
+  const int a = noff.v[b + 1] - noff.v[b];
+  if (!replace_T && a <= kIncMax && a <= p.window &&
+      vocab_apply_incremental(p, b, new_ids + noff.v[b], a, reinterpret_cast<int*>(lds)))
+    return;
   load_bitmaps(p, b, wb, tb, replace_T);
-  vocab_apply_body(p, b, new_ids + noff.v[b], noff.v[b + 1] - noff.v[b], topk + toff.v[b], toff.v[b + 1] - toff.v[b],
-                   replace_T, wb, tb, sc, 0);
+  vocab_apply_body(p, b, new_ids + noff.v[b], a, topk + toff.v[b], toff.v[b + 1] - toff.v[b], replace_T, wb, tb, sc, 0);
 }
 
 // Eq. 3 with the candidate set built on the device: the ids of cand[b][0..per_seq) (for instance the

@@ -229,6 +229,7 @@ __device__ __forceinline__ void load_bitmaps(const VocabPtrs& p, int b, uint32_t
 // caller then takes the general path); the decision is uniform over the workgroup.
 constexpr int kIncMax = 16;
 constexpr int kIncPass = 4 * kVocabThreads;   // list entries per pass
+constexpr int kIncLdsInts = 4 * kIncMax + 4;  // LDS the route needs: changes, offsets, three scalars
 
 __device__ __forceinline__ bool vocab_apply_incremental(const VocabPtrs& p, int b, const int32_t* src, int a, int* sh) {
   const int tid = threadIdx.x, lane = tid & 63;
@@ -263,10 +264,9 @@ __device__ __forceinline__ bool vocab_apply_incremental(const VocabPtrs& p, int 
   if (n_evict < 0) n_evict = 0;
   int oldest = pos - fill;
   if (oldest < 0) oldest += W;
-  int* sR = sh;                              // ids that left the active set
-  int* sA = sh + 2 * kIncMax;                // ids that entered it
-  int* sO = sh + 4 * kIncMax;                // per entered id: (entered ids below it) - (left ids below it)
-  int* sN = sh + 6 * kIncMax;                // counts
+  int* sC = sh;                              // ids that left the active set, then ids that entered it (<= 2*kIncMax)
+  int* sO = sh + 2 * kIncMax;                // per entered id: (entered ids below it) - (left ids below it)
+  int* sN = sh + 4 * kIncMax;                // how many left, how many entered, the lowest of them
   int bad = 0;
 
   if (tid < 64) {
@@ -314,26 +314,36 @@ __device__ __forceinline__ bool vocab_apply_incremental(const VocabPtrs& p, int 
     const int av = (entered && !(tw & bit)) ? id : INT_MAX;
     const unsigned long long mr = __ballot(r != INT_MAX), ma = __ballot(av != INT_MAX);
     const unsigned long long lower = (1ull << lane) - 1ull;
-    if (r != INT_MAX) sR[__popcll(mr & lower)] = r;
-    int o = 0;
-    for (unsigned long long m = mr; m; m &= m - 1ull) o -= __builtin_amdgcn_readlane(r, __ffsll((long long)m) - 1) < av ? 1 : 0;
-    for (unsigned long long m = ma; m; m &= m - 1ull) o += __builtin_amdgcn_readlane(av, __ffsll((long long)m) - 1) < av ? 1 : 0;
+    const int nR = __popcll(mr);
+    if (r != INT_MAX) sC[__popcll(mr & lower)] = r;
+    int o = 0, lowest = INT_MAX;
+    for (unsigned long long m = mr; m; m &= m - 1ull) {
+      const int x = __builtin_amdgcn_readlane(r, __ffsll((long long)m) - 1);
+      o -= x < av ? 1 : 0;
+      lowest = min(lowest, x);
+    }
+    for (unsigned long long m = ma; m; m &= m - 1ull) {
+      const int x = __builtin_amdgcn_readlane(av, __ffsll((long long)m) - 1);
+      o += x < av ? 1 : 0;
+      lowest = min(lowest, x);
+    }
     if (av != INT_MAX) {
       const int slot = __popcll(ma & lower);
-      sA[slot] = av;
+      sC[nR + slot] = av;
       sO[slot] = o;
     }
     if (lane == 0) {
-      sN[0] = __popcll(mr);
+      sN[0] = nR;
       sN[1] = __popcll(ma);
+      sN[2] = lowest;
     }
   }
   __syncthreads();
-  const int nR = sN[0], nA = sN[1];
+  const int nR = sN[0], nA = sN[1], lowest = sN[2];
   if (nR + nA) {
-    int lowest = INT_MAX;
-    for (int q = 0; q < nR; ++q) lowest = min(lowest, sR[q]);
-    for (int q = 0; q < nA; ++q) lowest = min(lowest, sA[q]);
+    // lane q (mod 32) of every wavefront keeps change q and its offset in registers: the loops below read
+    // them with readlane instead of waiting for LDS once per change
+    const int chg = sC[lane & (2 * kIncMax - 1)], chgo = sO[lane & (2 * kIncMax - 1)];
     const int passes = n_old / kIncPass + 1;
     for (int pass = 0; pass < passes; ++pass) {
       int4 qn = make_int4(INT_MAX, INT_MAX, INT_MAX, INT_MAX);
@@ -352,13 +362,13 @@ __device__ __forceinline__ bool vocab_apply_incremental(const VocabPtrs& p, int 
         // most one thread per change) is worked out entry by entry on top of that
         int m0 = 0, inside = 0;
         for (int q = 0; q < nR; ++q) {
-          const int x = __builtin_amdgcn_readfirstlane(sR[q]);
+          const int x = __builtin_amdgcn_readlane(chg, q);
           const int lt0 = x < xs[0] ? 1 : 0;
           m0 -= lt0;
           inside += (x < xs[4] ? 1 : 0) - lt0;
         }
         for (int q = 0; q < nA; ++q) {
-          const int x = __builtin_amdgcn_readfirstlane(sA[q]);
+          const int x = __builtin_amdgcn_readlane(chg, nR + q);
           const int lt0 = x < xs[0] ? 1 : 0;
           m0 += lt0;
           inside += (x < xs[4] ? 1 : 0) - lt0;
@@ -367,7 +377,7 @@ __device__ __forceinline__ bool vocab_apply_incremental(const VocabPtrs& p, int 
         bool dead[4] = {false, false, false, false};
         if (inside != 0 || (head && m0 != 0)) {
           for (int q = 0; q < nR; ++q) {
-            const int x = __builtin_amdgcn_readfirstlane(sR[q]);
+            const int x = __builtin_amdgcn_readlane(chg, q);
             if (x >= xs[0] && x < xs[4]) {
 #pragma unroll
               for (int i = 0; i < 4; ++i) {
@@ -377,8 +387,8 @@ __device__ __forceinline__ bool vocab_apply_incremental(const VocabPtrs& p, int 
             }
           }
           for (int q = 0; q < nA; ++q) {
-            const int x = __builtin_amdgcn_readfirstlane(sA[q]);
-            const int below = __builtin_amdgcn_readfirstlane(sO[q]);
+            const int x = __builtin_amdgcn_readlane(chg, nR + q);
+            const int below = __builtin_amdgcn_readlane(chgo, q);
             if (x >= xs[0] && x < xs[4]) {
 #pragma unroll
               for (int i = 0; i < 4; ++i) {
@@ -600,6 +610,7 @@ __global__ __launch_bounds__(kVocabThreads) void vocab_fifo_append_unique_kernel
 
 hipError_t vocab_configure(nanospec_state* st) {
   st->vocab_lds_bytes = (2 * st->vp.nwords + 32) * 4;
+  if (st->vocab_lds_bytes < kIncLdsInts * 4) st->vocab_lds_bytes = kIncLdsInts * 4;   // the list-patching route's scratch
   // candidates per call are bounded by what is left of the 160 KB of LDS after three bitmaps
   st->unique_cap = (160 * 1024 - 512) / 4 - (3 * st->vp.nwords + 32 + kVocabThreads);
   if (st->unique_cap < st->m_cap * st->k_cap) return hipErrorInvalidValue;

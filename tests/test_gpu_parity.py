@@ -143,6 +143,64 @@ def test_edge_cases_vocab():
     st.close()
 
 
+@pytest.mark.parametrize("V,W,distinct", [(60000, 20000, 13000), (5000, 4096, 5000), (300, 37, 300), (64, 64, 64)])
+def test_short_appends_patch_the_list(V, W, distinct):
+    """Updates of at most 16 ids with T untouched take the list-patching route: ids below the first and
+    above the last entry, ids that T holds, ids that leave and come back in one call, duplicates, ids out of
+    range, lists of several passes, a list at its capacity (V = 64: the general route takes over) -- the
+    active list equals the oracle's after every call, for three sequences with different streams."""
+    Bn, tcap = 3, 64
+    rng = np.random.default_rng(V + W)
+    st = B.State(V, 64, Bn, W, tcap, 4, 8)
+    orc = [oracle.Vocab(V, W) for _ in range(Bn)]
+    ctx = [rng.integers(V // 10, V // 10 + distinct * 8 // 10, size=W + 50).astype(np.int32) % V for _ in range(Bn)]
+    T = [rng.integers(0, V, size=tcap).astype(np.int32) for _ in range(Bn)]
+    f, off = csr(ctx)
+    tf, toff = csr(T)
+    B.nanospec_vocab_init(st.h, dev_ids(f), off, dev_ids(tf), toff)
+    for b in range(Bn):
+        orc[b].init(ctx[b], T[b])
+    bad_expected = False
+    for step in range(120):
+        new = []
+        for b in range(Bn):
+            a = int(rng.integers(0, 17))
+            kind = int(rng.integers(0, 6))
+            if kind == 0:
+                x = rng.integers(0, max(1, V // 10), size=a)              # below the context's range
+            elif kind == 1:
+                x = rng.integers(V - max(1, V // 20), V, size=a)          # above it
+            elif kind == 2:
+                x = rng.choice(T[b], size=a)                              # ids that T holds
+            elif kind == 3:
+                x = np.repeat(rng.integers(0, V, size=1), a)              # one id, many times
+            elif kind == 4:
+                x = orc[b].active()[:a] if len(orc[b].active()) else rng.integers(0, V, size=a)   # the lowest active ids
+            else:
+                x = rng.integers(0, V, size=a)
+            x = np.asarray(x, np.int32).copy()
+            if step % 37 == 5 and a:
+                x[0] = V + 3                                              # out of range: flagged, holds a position
+                bad_expected = True
+            new.append(x)
+        f, off = csr(new)
+        B.nanospec_vocab_update(st.h, dev_ids(f), off)
+        for b in range(Bn):
+            orc[b].update(new[b], None)
+        act = st.read_active()
+        for b in range(Bn):
+            assert np.array_equal(act[b], orc[b].active()), (step, b)
+    assert (B.nanospec_last_device_error(st.h) == B.DEV_BAD_ID) == bad_expected
+    # the general route afterwards sees a consistent state: a T replacement rebuilds the list from the bitmaps
+    B.nanospec_vocab_update(st.h, None, [0] * (Bn + 1), dev_ids(tf), toff)
+    for b in range(Bn):
+        orc[b].update([], T[b])
+    act = st.read_active()
+    for b in range(Bn):
+        assert np.array_equal(act[b], orc[b].active())
+    st.close()
+
+
 def test_vocab_fuzz_ragged_batch():
     rng = np.random.default_rng(5)
     V, W, Bn = 5000, 37, 7

@@ -89,22 +89,34 @@ __device__ __forceinline__ int compact_bitmap(Word4Fn word4, int nwords, int32_t
     off += (w < wave ? t.x : 0) + (w + 1 < wave ? t.y : 0) + (w + 2 < wave ? t.z : 0) + (w + 3 < wave ? t.w : 0);
     total += t.x + t.y + t.z + t.w;
   }
-  auto emit = [&](uint32_t x, int base) {
-    while (x) {
-      const int bit = __ffs(x) - 1;
-      if (off < cap) out[off] = base + bit;
-      ++off;
-      x &= x - 1;
+  // Emission costs one trip round a short loop per set bit and wavefront-wide per word (the lane with the
+  // most bits sets the pace), on a workgroup whose sixteen wavefronts share four SIMDs: it is bound by
+  // instruction issue, so the loop is kept to the bare minimum -- two words at a time as one 64-bit
+  // value, an unsigned 32-bit list index (base register + offset addressing), and the capacity test
+  // hoisted out (the list fits unless T is larger than the state was created for).
+  uint32_t uo = (uint32_t)off;
+  const bool fits = total <= cap;
+  auto emit2 = [&](uint32_t lo, uint32_t hi, int base) {
+    unsigned long long x = ((unsigned long long)hi << 32) | lo;
+    if (fits) {
+      while (x) {
+        out[uo++] = base + __ffsll((long long)x) - 1;
+        x &= x - 1ull;
+      }
+    } else {
+      while (x) {
+        if (uo < (uint32_t)cap) out[uo] = base + __ffsll((long long)x) - 1;
+        ++uo;
+        x &= x - 1ull;
+      }
     }
   };
 #pragma unroll
-  for (int q = 0; q < kKeep; ++q) emit(keep[q], (w0 + q) * 32);   // words past the end are zero
+  for (int q = 0; q < kKeep; q += 2) emit2(keep[q], keep[q + 1], (w0 + q) * 32);   // words past the end are zero
   for (int i = w0 + kKeep; i < w0 + wpt && i < nwords; i += 4) {
     const uint4 x = word4(i);
-    emit(x.x, i * 32);
-    emit(x.y, (i + 1) * 32);
-    emit(x.z, (i + 2) * 32);
-    emit(x.w, (i + 3) * 32);
+    emit2(x.x, x.y, i * 32);
+    emit2(x.z, x.w, (i + 2) * 32);
   }
   return total;
 }

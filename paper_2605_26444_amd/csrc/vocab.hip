@@ -8,7 +8,8 @@
 // leaves or enters the window; the decrement that reaches zero clears the bit and, after a barrier,
 // every entering id sets it (so an id that is evicted and re-appended in the same call ends up
 // correct whatever order the atomics landed in), and the union bitmap is compacted with popcounts
-// and a workgroup prefix scan.  Both bitmaps live in LDS during the kernel.
+// and a workgroup prefix scan.  Both bitmaps live in LDS during the kernel.  A short append that leaves T
+// alone -- the decoding step -- does not rebuild the list: it patches it in place (vocab_apply_incremental).
 // The paper's other description of the same state -- a first-in first-out queue of at most `window`
 // distinct ids -- is the second half of this file (vocab_fifo_kernel).
 #include <limits.h>

@@ -269,8 +269,13 @@ __global__ __launch_bounds__(256 * NRG) void head_quad_kernel(const uint16_t* __
   // without waiting for the row count: the list is allocated to its capacity, a stale id is clamped
   // into the matrix and its product is never stored.  (Measured on MI355X: fetching them through
   // the vector path beats the scalar cache here by ~0.5 us, and leaving early on the row count
-  // costs ~1.4 us because the hidden-row loads then sink below the wait for the count; workgroups
-  // past the end therefore run through with their weight loads masked off.)
+  // costs ~1.4 us because the hidden-row loads then sink below the wait for the count.)
+  // Every load below is unconditional -- out-of-range rows and columns are clamped to valid addresses and
+  // masked by arithmetic (row groups past the end all read the first 16 bytes of row 0, which costs next to nothing) -- because a
+  // load under a branch makes the outstanding-load count unknowable at compile time: the wait for the
+  // ids then becomes a wait for the hidden rows as well, and the weight loads queue behind both.  The row
+  // count comes through the vector path too, right behind the ids: scalar loads return out of order, so
+  // waiting for a kernel argument would wait for the count before the first hidden-row load is issued.
   int idr[RPG];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {                       // one 16-byte load per four rows (j0 and the row stride are multiples of 4)
@@ -281,14 +286,28 @@ __global__ __launch_bounds__(256 * NRG) void head_quad_kernel(const uint16_t* __
     idr[rt * 4 + 2] = v.z;
     idr[rt * 4 + 3] = v.w;
   }
-  const int n = n_dev ? n_dev[b] : n_fixed;
+  // (Row groups of 8 rows -- the many-sequence, throughput-bound shape -- keep predicated loads: there
+  // the extra address arithmetic costs more than the earlier issue gains; 64 sequences 186 against 179 us.)
+  constexpr bool UNCOND = RT == 1;
+  int vzero = 0;
+  if (UNCOND) asm volatile("" : "+v"(vzero));             // a zero the compiler cannot see through: keeps the load below on the vector path
+  const int n = n_dev ? n_dev[b + vzero] : n_fixed;
 
+  bool hok[HPW];
   auto load_h = [&](int kb, u32x4(&hv)[HPW]) {
 #pragma unroll
     for (int ii = 0; ii < HPW; ++ii) {
-      const int i = rg * HPW + ii, mt = i / KS, t = i % KS;
-      const int m = mt * 4 + orow, c = kb + coff + t * 128;
-      hv[ii] = (i < HI && m < M && c < d) ? *reinterpret_cast<const u32x4*>(Hb + (int64_t)m * d + c) : zero;
+      if constexpr (UNCOND) {
+        const int i = rg * HPW + ii, ic = i < HI ? i : HI - 1, mt = ic / KS, t = ic % KS;
+        const int m = mt * 4 + orow, c = kb + coff + t * 128;
+        hok[ii] = m < M && c < d;
+        hv[ii] = *reinterpret_cast<const u32x4*>(Hb + (int64_t)(m < M ? m : M - 1) * d + (c < d ? c : 0));
+      } else {
+        const int i = rg * HPW + ii, mt = i / KS, t = i % KS;
+        const int m = mt * 4 + orow, c = kb + coff + t * 128;
+        hok[ii] = true;
+        hv[ii] = (i < HI && m < M && c < d) ? *reinterpret_cast<const u32x4*>(Hb + (int64_t)m * d + c) : zero;
+      }
     }
   };
   // this wavefront's share of the hidden rows of the first K-iteration depends on the arguments
@@ -301,9 +320,10 @@ __global__ __launch_bounds__(256 * NRG) void head_quad_kernel(const uint16_t* __
   for (int rt = 0; rt < RT; ++rt) {
     int64_t row = orow == 0 ? idr[rt * 4] : (orow == 1 ? idr[rt * 4 + 1] : (orow == 2 ? idr[rt * 4 + 2] : idr[rt * 4 + 3]));
     row = row < 0 ? 0 : (row >= V ? V - 1 : row);
+    if (UNCOND) row = j0 < n ? row : 0;
     wrow[rt] = W + row * d;
   }
-  const bool live = j0 < n;
+  const bool live = j0 < n;                               // a row group past the end reads one 16-byte piece of row 0 over and over
 
   f32x4 acc[RT][MT];
 #pragma unroll
@@ -320,12 +340,14 @@ __global__ __launch_bounds__(256 * NRG) void head_quad_kernel(const uint16_t* __
 #pragma unroll
       for (int t = 0; t < KS; ++t) {
         const int c = kb + coff + t * 128;
-        wv[rt][t] = (live && c < d) ? *reinterpret_cast<const u32x4*>(wrow[rt] + c) : zero;
+        if (UNCOND) wv[rt][t] = *reinterpret_cast<const u32x4*>(wrow[rt] + ((live && c < d) ? c : 0));   // columns past d meet zeros of H
+        else wv[rt][t] = (live && c < d) ? *reinterpret_cast<const u32x4*>(wrow[rt] + c) : zero;
       }
+    if (UNCOND) __builtin_amdgcn_sched_barrier(0);          // the masking of the hidden rows (a wait for them) stays below the weight loads
     if (kb != 0) __syncthreads();                           // the previous slice has been consumed
 #pragma unroll
     for (int ii = 0; ii < HPW; ++ii)
-      if (rg * HPW + ii < HI) *reinterpret_cast<u32x4*>(hs + (kq * HI + rg * HPW + ii) * 1024 + lane * 16) = hv[ii];
+      if (rg * HPW + ii < HI) *reinterpret_cast<u32x4*>(hs + (kq * HI + rg * HPW + ii) * 1024 + lane * 16) = (!UNCOND || hok[ii]) ? hv[ii] : zero;
     __syncthreads();
 #pragma unroll
     for (int t = 0; t < KS; ++t)

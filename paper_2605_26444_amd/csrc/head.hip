@@ -104,7 +104,7 @@ __device__ __forceinline__ float quad_sum(float x) {
 // several times the arithmetic the HBM stream can feed.
 // A workgroup of four wavefronts owns 4*RT rows; wavefront w takes columns [kb + w*128*KS, +128*KS)
 // per K-iteration; the four K-slices are summed in fixed order through LDS.
-template <int RT, int MT, int KS, int NW>
+template <int RT, int MT, int KS, int NW, bool FAST>
 __global__ __launch_bounds__(64 * NW) void head_quad_private_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
                                                         const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
                                                         int n_fixed, int V, int M, int d, int64_t ld, int64_t ids_stride,
@@ -122,14 +122,20 @@ __global__ __launch_bounds__(64 * NW) void head_quad_private_kernel(const uint16
   const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
   const uint16_t* Hb = H + (int64_t)b * M * d;
 
+  // FAST (chosen by the launcher): d is a whole number of K-iterations and M == 4*MT, so no load needs a
+  // bounds test and every address is a per-row base plus a compile-time offset -- two instructions per
+  // load instead of a branch and a dozen (the generic form spends ~600 instructions per wavefront on its
+  // 32 hidden-row loads before the first weight load is issued).
   auto load_h = [&](int kb, u32x4(&hv)[MT][KS]) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       const int m = mt * 4 + orow;
+      const uint16_t* hp = Hb + (int64_t)m * d + coff + kb;
 #pragma unroll
       for (int t = 0; t < KS; ++t) {
         const int c = kb + coff + t * 128;
-        hv[mt][t] = (c < d && m < M) ? *reinterpret_cast<const u32x4*>(Hb + (int64_t)m * d + c) : zero;
+        if (FAST) hv[mt][t] = *reinterpret_cast<const u32x4*>(hp + t * 128);
+        else hv[mt][t] = (c < d && m < M) ? *reinterpret_cast<const u32x4*>(Hb + (int64_t)m * d + c) : zero;
       }
     }
   };
@@ -138,14 +144,19 @@ __global__ __launch_bounds__(64 * NW) void head_quad_private_kernel(const uint16
   // count: the list is allocated to its capacity, a stale id is clamped into the matrix and its
   // product is never stored.
   int idr[ROWS];
+  if (ids) {                                              // one branch around all of them: the loads go out back to back
+    const int4* ip = reinterpret_cast<const int4*>(ids + b * ids_stride + j0);
 #pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-    const int4 v = ids ? *reinterpret_cast<const int4*>(ids + b * ids_stride + j0 + rt * 4)
-                       : make_int4(j0 + rt * 4, j0 + rt * 4 + 1, j0 + rt * 4 + 2, j0 + rt * 4 + 3);
-    idr[rt * 4] = v.x;
-    idr[rt * 4 + 1] = v.y;
-    idr[rt * 4 + 2] = v.z;
-    idr[rt * 4 + 3] = v.w;
+    for (int rt = 0; rt < RT; ++rt) {
+      const int4 v = ip[rt];
+      idr[rt * 4] = v.x;
+      idr[rt * 4 + 1] = v.y;
+      idr[rt * 4 + 2] = v.z;
+      idr[rt * 4 + 3] = v.w;
+    }
+  } else {
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) idr[r] = j0 + r;
   }
   const int n = n_dev ? n_dev[b] : n_fixed;
   // hidden rows of the first K-iteration depend on the arguments only: they stream in from L2
@@ -169,16 +180,20 @@ __global__ __launch_bounds__(64 * NW) void head_quad_private_kernel(const uint16
     for (int mt = 0; mt < MT; ++mt) acc[rt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   for (int kb = 0; kb < d; kb += NW * 128 * KS) {
-    if (kb + w * (128 * KS) >= d) break;
+    if (!FAST && kb + w * (128 * KS) >= d) break;
     u32x4 wv[RT][KS];
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt)
+    for (int rt = 0; rt < RT; ++rt) {
+      const uint16_t* wp = wrow[rt] + coff + kb;
 #pragma unroll
       for (int t = 0; t < KS; ++t) {
         const int c = kb + coff + t * 128;
-        wv[rt][t] = (c < d) ? *reinterpret_cast<const u32x4*>(wrow[rt] + c) : zero;
+        if (FAST) wv[rt][t] = *reinterpret_cast<const u32x4*>(wp + t * 128);
+        else wv[rt][t] = (c < d) ? *reinterpret_cast<const u32x4*>(wrow[rt] + c) : zero;
       }
+    }
     if (kb != 0) load_h(kb, hv);
+    if (FAST) __builtin_amdgcn_sched_barrier(0);            // all loads of the iteration stay in front of its first MFMA
 #pragma unroll
     for (int t = 0; t < KS; ++t)
 #pragma unroll
@@ -219,8 +234,12 @@ static hipError_t run_quad_private(const uint16_t* W, const uint16_t* H, const i
   const int tiles = (cap_rows + 4 * RT - 1) / (4 * RT);
   const int seq_first = batch > 1 && tiles <= 65535;
   const dim3 grid = seq_first ? dim3(batch, tiles, 1) : dim3(tiles, 1, batch);
-  head_quad_private_kernel<RT, MT, KS, NW><<<grid, 64 * NW, 0, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits,
-                                                                    seq_first);
+  if (d % (NW * 128 * KS) == 0 && M == 4 * MT)
+    head_quad_private_kernel<RT, MT, KS, NW, true><<<grid, 64 * NW, 0, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride,
+                                                                            logits, seq_first);
+  else
+    head_quad_private_kernel<RT, MT, KS, NW, false><<<grid, 64 * NW, 0, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride,
+                                                                             logits, seq_first);
   return hipGetLastError();
 }
 
@@ -277,14 +296,19 @@ __global__ __launch_bounds__(256 * NRG) void head_quad_kernel(const uint16_t* __
   // count comes through the vector path too, right behind the ids: scalar loads return out of order, so
   // waiting for a kernel argument would wait for the count before the first hidden-row load is issued.
   int idr[RPG];
+  if (ids) {                                              // one 16-byte load per four rows (j0 and the row stride are multiples of 4)
+    const int4* ip = reinterpret_cast<const int4*>(ids + b * ids_stride + j0);
 #pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {                       // one 16-byte load per four rows (j0 and the row stride are multiples of 4)
-    const int4 v = ids ? *reinterpret_cast<const int4*>(ids + b * ids_stride + j0 + rt * 4)
-                       : make_int4(j0 + rt * 4, j0 + rt * 4 + 1, j0 + rt * 4 + 2, j0 + rt * 4 + 3);
-    idr[rt * 4] = v.x;
-    idr[rt * 4 + 1] = v.y;
-    idr[rt * 4 + 2] = v.z;
-    idr[rt * 4 + 3] = v.w;
+    for (int rt = 0; rt < RT; ++rt) {
+      const int4 v = ip[rt];
+      idr[rt * 4] = v.x;
+      idr[rt * 4 + 1] = v.y;
+      idr[rt * 4 + 2] = v.z;
+      idr[rt * 4 + 3] = v.w;
+    }
+  } else {
+#pragma unroll
+    for (int r = 0; r < RPG; ++r) idr[r] = j0 + r;
   }
   // (Row groups of 8 rows -- the many-sequence, throughput-bound shape -- keep predicated loads: there
   // the extra address arithmetic costs more than the earlier issue gains; 64 sequences 186 against 179 us.)

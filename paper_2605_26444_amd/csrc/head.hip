@@ -471,7 +471,13 @@ static hipError_t run_quad_auto(const uint16_t* W, const uint16_t* H, const int3
 //   LOOPK = false: split-K -- slice = blockIdx.y, partial products go to that slice's plane and
 //                  head_splitk_reduce_kernel adds the planes in slice order (few rows: the rows
 //                  alone cannot fill the chip; deterministic because the order is fixed).
-template <int MT, bool LOOPK>
+//   FAST (chosen by the launcher): M == 16*MT and d a whole number of slices, so no load needs a bounds
+//   test; rows past the end read row 0 instead of being skipped, the row count arrives on the vector
+//   path behind the ids, and every address is a base plus a lane offset.  The generic form spends ~25
+//   instructions and a branch on each of its 32 loads per slice (~860 instructions before the last weight
+//   load of the first slice is issued) and, because of the branches, waits for all hidden-row loads
+//   before it issues the first weight load.
+template <int MT, bool LOOPK, bool FAST>
 __global__ __launch_bounds__(256) void head_tile64_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
                                                           const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
                                                           int n_fixed, int V, int M, int d, int64_t ld, int64_t ids_stride,
@@ -489,27 +495,50 @@ __global__ __launch_bounds__(256) void head_tile64_kernel(const uint16_t* __rest
   // one id per lane (capacity-bounded, not waiting for the row count), handed out by readlane
   int myid = j0 + (lane & 15);
   if (ids) myid = ids[b * ids_stride + j0 + (lane & 15)];
-  const int n = n_dev ? n_dev[b] : n_fixed;
-  // split-K launches are sized by capacity: tiles past n leave before they pull their hidden-row slice
-  // (measured neutral at n close to capacity, and it spares the L2 when n is far below it)
-  if (!LOOPK && (int)blockIdx.x * 64 >= n) return;
+  int vzero = 0;
+  if (FAST) asm volatile("" : "+v"(vzero));               // keeps the row count's load on the vector path, in order behind the ids
+  const int nv = n_dev ? n_dev[b + vzero] : n_fixed;
   u32x4 hv[16], wv[16];
+  int n = nv;
   auto load_slice = [&](int sl) {
-    const int c = sl * 512 + lane * 8;
-    const bool cok = c < d;
+    if constexpr (FAST) {
+      const uint32_t cb = (uint32_t)(sl * 512 + lane * 8) * 2u;            // byte offset inside a row
+      const char* hp = reinterpret_cast<const char*>(H + ((int64_t)b * M + w * 16) * d) + cb;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int m = w * 16 + r;
-      hv[r] = (cok && m < M) ? *reinterpret_cast<const u32x4*>(H + ((int64_t)b * M + m) * d + c) : zero;
-    }
+      for (int r = 0; r < 16; ++r) hv[r] = *reinterpret_cast<const u32x4*>(hp + (int64_t)r * d * 2);
+      __builtin_amdgcn_sched_barrier(0);                                  // the hidden-row loads go out before the ids are waited for
+      n = __builtin_amdgcn_readfirstlane(nv);
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      int64_t row = __builtin_amdgcn_readlane(myid, r);
-      row = row < 0 ? 0 : (row >= V ? V - 1 : row);
-      wv[r] = (cok && j0 + r < n) ? *reinterpret_cast<const u32x4*>(W + row * d + c) : zero;
+      for (int r = 0; r < 16; ++r) {
+        int row = __builtin_amdgcn_readlane(myid, r);
+        row = row < 0 ? 0 : (row >= V ? V - 1 : row);
+        row = j0 + r < n ? row : 0;                                       // rows past the end: row 0, never stored
+        const char* rp = reinterpret_cast<const char*>(W + (int64_t)row * d);
+        wv[r] = *reinterpret_cast<const u32x4*>(rp + cb);
+      }
+      __builtin_amdgcn_sched_barrier(0);                                  // ... and all loads of the slice before anything waits for one
+    } else {
+      const int c = sl * 512 + lane * 8;
+      const bool cok = c < d;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = w * 16 + r;
+        hv[r] = (cok && m < M) ? *reinterpret_cast<const u32x4*>(H + ((int64_t)b * M + m) * d + c) : zero;
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        int64_t row = __builtin_amdgcn_readlane(myid, r);
+        row = row < 0 ? 0 : (row >= V ? V - 1 : row);
+        wv[r] = (cok && j0 + r < n) ? *reinterpret_cast<const u32x4*>(W + row * d + c) : zero;
+      }
     }
   };
+  // split-K launches are sized by capacity: tiles past n leave before they pull their hidden-row slice
+  // (measured neutral at n close to capacity, and it spares the L2 when n is far below it); the FAST form
+  // learns n only with the ids and leaves after its first slice's loads
+  if (!FAST && !LOOPK && (int)blockIdx.x * 64 >= n) return;
   load_slice(s0);
+  if (FAST && !LOOPK && (int)blockIdx.x * 64 >= n) return;
   const int rd_off = (lane & 15) * STRB + (lane >> 4) * 16;
   f32x4 acc[MT];
 #pragma unroll
@@ -574,12 +603,12 @@ __global__ __launch_bounds__(256) void head_splitk_reduce_kernel(const float* __
   *reinterpret_cast<f32x4*>(logits + ((int64_t)b * M + m) * ld + j) = s;
 }
 
-template <int MT, bool LOOPK>
+template <int MT, bool LOOPK, bool FAST>
 static hipError_t tile64_configure() {
   static PerDeviceOnce once;
   int dev;
   if (once.needed(&dev)) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_tile64_kernel<MT, LOOPK>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_tile64_kernel<MT, LOOPK, FAST>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 16 * (1024 + 16));
     if (e != hipSuccess) return e;
     once.mark(dev);
@@ -592,10 +621,12 @@ static hipError_t run_splitk(const uint16_t* W, const uint16_t* H, const int32_t
                              int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride, float* logits,
                              float* partial, int S, hipStream_t s) {
   constexpr int LDS = 4 * 16 * (1024 + 16);
-  hipError_t e = tile64_configure<MT, false>();
+  const bool fast = M == 16 * MT && d % 512 == 0;
+  hipError_t e = fast ? tile64_configure<MT, false, true>() : tile64_configure<MT, false, false>();
   if (e != hipSuccess) return e;
-  head_tile64_kernel<MT, false><<<dim3((cap_rows + 63) / 64, S, batch), 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows,
-                                                                                    ids_stride, partial);
+  const dim3 grid((cap_rows + 63) / 64, S, batch);
+  if (fast) head_tile64_kernel<MT, false, true><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial);
+  else head_tile64_kernel<MT, false, false><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   head_splitk_reduce_kernel<<<dim3((cap_rows / 4 + 255) / 256, M, batch), 256, 0, s>>>(partial, n_dev, S, M, cap_rows, ld,
@@ -608,10 +639,12 @@ static hipError_t run_tile64(const uint16_t* W, const uint16_t* H, const int32_t
                              int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride,
                              float* logits, hipStream_t s) {
   constexpr int LDS = 4 * 16 * (1024 + 16);
-  hipError_t e = tile64_configure<MT, true>();
+  const bool fast = M == 16 * MT && d % 512 == 0;
+  hipError_t e = fast ? tile64_configure<MT, true, true>() : tile64_configure<MT, true, false>();
   if (e != hipSuccess) return e;
-  head_tile64_kernel<MT, true><<<dim3((cap_rows + 63) / 64, 1, batch), 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld,
-                                                                                   ids_stride, logits);
+  const dim3 grid((cap_rows + 63) / 64, 1, batch);
+  if (fast) head_tile64_kernel<MT, true, true><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
+  else head_tile64_kernel<MT, true, false><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
   return hipGetLastError();
 }
 

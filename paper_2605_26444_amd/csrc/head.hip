@@ -508,12 +508,17 @@ __global__ __launch_bounds__(256) void head_tile64_kernel(const uint16_t* __rest
       for (int r = 0; r < 16; ++r) hv[r] = *reinterpret_cast<const u32x4*>(hp + (int64_t)r * d * 2);
       __builtin_amdgcn_sched_barrier(0);                                  // the hidden-row loads go out before the ids are waited for
       n = __builtin_amdgcn_readfirstlane(nv);
+      // lane r (mod 16) works out the byte offset of row r once; the wavefront then needs two readlanes,
+      // a scalar add and a base-register + lane-offset load per row
+      int mrow = myid < 0 ? 0 : (myid >= V ? V - 1 : myid);
+      mrow = j0 + (lane & 15) < n ? mrow : 0;                               // rows past the end: row 0, never stored
+      const uint64_t ro = (uint64_t)(uint32_t)mrow * (uint64_t)(uint32_t)(d * 2);
+      const uint32_t rol = (uint32_t)ro, roh = (uint32_t)(ro >> 32);
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        int row = __builtin_amdgcn_readlane(myid, r);
-        row = row < 0 ? 0 : (row >= V ? V - 1 : row);
-        row = j0 + r < n ? row : 0;                                       // rows past the end: row 0, never stored
-        const char* rp = reinterpret_cast<const char*>(W + (int64_t)row * d);
+        const uint64_t o = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)roh, r) << 32) |
+                           (uint32_t)__builtin_amdgcn_readlane((int)rol, r);
+        const char* rp = reinterpret_cast<const char*>(W) + o;
         wv[r] = *reinterpret_cast<const u32x4*>(rp + cb);
       }
       __builtin_amdgcn_sched_barrier(0);                                  // ... and all loads of the slice before anything waits for one

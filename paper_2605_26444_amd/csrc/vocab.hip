@@ -242,116 +242,66 @@ __device__ __forceinline__ void load_bitmaps(const VocabPtrs& p, int b, uint32_t
 // caller then takes the general path); the decision is uniform over the workgroup.
 constexpr int kIncMax = 16;
 constexpr int kIncPass = 4 * kVocabThreads;   // list entries per pass
-constexpr int kIncLdsInts = 4 * kIncMax + 4;  // LDS the route needs: changes, offsets, three scalars
+constexpr int kIncLdsInts = 4 * kIncMax + 4;  // LDS the route needs: changes, offsets, four scalars
 
-__device__ __forceinline__ bool vocab_apply_incremental(const VocabPtrs& p, int b, const int32_t* src, int a, int* sh) {
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int V = p.V, W = p.window, cap = p.cap;
-  int32_t* ids = p.ids + (size_t)b * cap;
-  uint32_t* gw = p.wbit + (size_t)b * p.nwords;
-  const uint32_t* gt = p.tbit + (size_t)b * p.nwords;
-  uint32_t* cnt = p.cnt + (size_t)b * V;
-  int32_t* ring = p.ring + (size_t)b * W;
-  // everything that does not depend on the state's scalars is requested first
-  const int n_old = p.n[b], pos = p.pos[b], fill = p.fill[b];
-  const bool ap = tid >= kIncMax && tid < kIncMax + a;        // this thread appends src[tid - kIncMax]
-  int v = -1;
-  if (ap) v = src[tid - kIncMax];
-  int4 q0 = make_int4(INT_MAX, INT_MAX, INT_MAX, INT_MAX);
-  int q0n = INT_MAX;
-  if (4 * tid < cap) q0 = *reinterpret_cast<const int4*>(ids + 4 * tid);   // cap is a multiple of 4
-  if (4 * tid + 4 < cap) q0n = ids[4 * tid + 4];
-  if (n_old + a > cap) return false;
-  auto mask_pass = [&](int pass, const int4& q, int nx, int (&x)[5]) {
-    const int j0 = pass * kIncPass + 4 * tid;
-    x[0] = j0 < n_old ? q.x : INT_MAX;
-    x[1] = j0 + 1 < n_old ? q.y : INT_MAX;
-    x[2] = j0 + 2 < n_old ? q.z : INT_MAX;
-    x[3] = j0 + 3 < n_old ? q.w : INT_MAX;
-    x[4] = j0 + 4 < n_old ? nx : INT_MAX;
-  };
-  int xs[5];
-  mask_pass(0, q0, q0n, xs);
+// The part of a list patch that does not depend on the stream policy.
+struct IncScratch {
+  int* sC;   // ids that left the active set, then ids that entered it (<= 2*kIncMax)
+  int* sO;   // per entered id: (entered ids below it) - (left ids below it)
+  int* sN;   // how many left, how many entered, the lowest of them
+  __device__ explicit IncScratch(int* sh) : sC(sh), sO(sh + 2 * kIncMax), sN(sh + 4 * kIncMax) {}
+};
 
-  int n_evict = fill + a - W;                // a <= W here
-  if (n_evict < 0) n_evict = 0;
-  int oldest = pos - fill;
-  if (oldest < 0) oldest += W;
-  int* sC = sh;                              // ids that left the active set, then ids that entered it (<= 2*kIncMax)
-  int* sO = sh + 2 * kIncMax;                // per entered id: (entered ids below it) - (left ids below it)
-  int* sN = sh + 4 * kIncMax;                // how many left, how many entered, the lowest of them
-  int bad = 0;
-
-  if (tid < 64) {
-    int id = -1;
-    if (ap) {
-      if ((unsigned)v < (unsigned)V) id = v;
-      else bad = 1;
-    } else if (lane < n_evict) {
-      int slot = oldest + lane;
-      if (slot >= W) slot -= W;
-      id = ring[slot];
-    }
-    const bool valid = id >= 0;
-    uint32_t tw = 0u, oldc = 0u;
-    if (valid) {
-      tw = gt[id >> 5];
-      oldc = cnt[id];
-    }
-    // net change of this lane's id over all lanes, and whether an earlier lane holds the same id
-    int total = 0;
-    bool first = true;
-    for (int j = 0; j < n_evict; ++j) {
-      const bool same = valid && __builtin_amdgcn_readlane(id, j) == id;
-      total -= same ? 1 : 0;
-      first = first && !(same && j < lane);
-    }
-    for (int j = kIncMax; j < kIncMax + a; ++j) {
-      const bool same = valid && __builtin_amdgcn_readlane(id, j) == id;
-      total += same ? 1 : 0;
-      first = first && !(same && j < lane);
-    }
-    if (ap) {
-      int slot = pos + (lane - kIncMax);
-      if (slot >= W) slot -= W;
-      ring[slot] = id;                         // the leaving entries are in registers by now; -1 for an id out of range
-    }
-    const bool lead = valid && first;
-    const uint32_t newc = oldc + (uint32_t)total;
-    const uint32_t bit = 1u << (id & 31);
-    if (lead && total != 0) cnt[id] = newc;
-    const bool left = lead && oldc != 0u && newc == 0u, entered = lead && oldc == 0u && newc != 0u;
-    if (left) atomicAnd(&gw[id >> 5], ~bit);   // another lane may own a different bit of the same word
-    if (entered) atomicOr(&gw[id >> 5], bit);
-    const int r = (left && !(tw & bit)) ? id : INT_MAX;
-    const int av = (entered && !(tw & bit)) ? id : INT_MAX;
-    const unsigned long long mr = __ballot(r != INT_MAX), ma = __ballot(av != INT_MAX);
-    const unsigned long long lower = (1ull << lane) - 1ull;
-    const int nR = __popcll(mr);
-    if (r != INT_MAX) sC[__popcll(mr & lower)] = r;
-    int o = 0, lowest = INT_MAX;
-    for (unsigned long long m = mr; m; m &= m - 1ull) {
-      const int x = __builtin_amdgcn_readlane(r, __ffsll((long long)m) - 1);
-      o -= x < av ? 1 : 0;
-      lowest = min(lowest, x);
-    }
-    for (unsigned long long m = ma; m; m &= m - 1ull) {
-      const int x = __builtin_amdgcn_readlane(av, __ffsll((long long)m) - 1);
-      o += x < av ? 1 : 0;
-      lowest = min(lowest, x);
-    }
-    if (av != INT_MAX) {
-      const int slot = __popcll(ma & lower);
-      sC[nR + slot] = av;
-      sO[slot] = o;
-    }
-    if (lane == 0) {
-      sN[0] = nR;
-      sN[1] = __popcll(ma);
-      sN[2] = lowest;
-    }
+// First wavefront: lane l holds an id that left the active set (r) and/or one that entered it (av), INT_MAX for
+// none; the lists, the rank of every entered id among the changes and the counts go to LDS.
+__device__ __forceinline__ void inc_publish(int r, int av, int lane, const IncScratch& sc) {
+  int* sC = sc.sC;
+  int* sO = sc.sO;
+  int* sN = sc.sN;
+  const unsigned long long mr = __ballot(r != INT_MAX), ma = __ballot(av != INT_MAX);
+  const unsigned long long lower = (1ull << lane) - 1ull;
+  const int nR = __popcll(mr);
+  if (r != INT_MAX) sC[__popcll(mr & lower)] = r;
+  int o = 0, lowest = INT_MAX;
+  for (unsigned long long m = mr; m; m &= m - 1ull) {
+    const int x = __builtin_amdgcn_readlane(r, __ffsll((long long)m) - 1);
+    o -= x < av ? 1 : 0;
+    lowest = min(lowest, x);
   }
-  __syncthreads();
+  for (unsigned long long m = ma; m; m &= m - 1ull) {
+    const int x = __builtin_amdgcn_readlane(av, __ffsll((long long)m) - 1);
+    o += x < av ? 1 : 0;
+    lowest = min(lowest, x);
+  }
+  if (av != INT_MAX) {
+    const int slot = __popcll(ma & lower);
+    sC[nR + slot] = av;
+    sO[slot] = o;
+  }
+  if (lane == 0) {
+    sN[0] = nR;
+    sN[1] = __popcll(ma);
+    sN[2] = lowest;
+  }
+}
+
+// Entries 4*tid .. 4*tid+4 of pass `pass` of the list (the fifth one is the next thread's first), INT_MAX past the end.
+__device__ __forceinline__ void inc_mask(int pass, int tid, int n_old, const int4& q, int nx, int (&x)[5]) {
+  const int j0 = pass * kIncPass + 4 * tid;
+  x[0] = j0 < n_old ? q.x : INT_MAX;
+  x[1] = j0 + 1 < n_old ? q.y : INT_MAX;
+  x[2] = j0 + 2 < n_old ? q.z : INT_MAX;
+  x[3] = j0 + 3 < n_old ? q.w : INT_MAX;
+  x[4] = j0 + 4 < n_old ? nx : INT_MAX;
+}
+
+// All threads, after the barrier that follows inc_publish: move the list entries (xs = this thread's entries of
+// the first pass) and write the entered ids.  Returns the change of the list's length.
+__device__ __forceinline__ int inc_patch(int32_t* ids, int cap, int n_old, int (&xs)[5], const IncScratch& sc) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int* sC = sc.sC;
+  const int* sO = sc.sO;
+  const int* sN = sc.sN;
   const int nR = sN[0], nA = sN[1], lowest = sN[2];
   if (nR + nA) {
     // lane q (mod 32) of every wavefront keeps change q and its offset in registers: the loops below read
@@ -416,11 +366,88 @@ __device__ __forceinline__ bool vocab_apply_incremental(const VocabPtrs& p, int 
         for (int i = 0; i < 4; ++i)
           if (xs[i] != INT_MAX && !dead[i] && mv[i] != 0) ids[j0 + i + mv[i]] = xs[i];
       }
-      mask_pass(pass + 1, qn, qnn, xs);
+      inc_mask(pass + 1, tid, n_old, qn, qnn, xs);
     }
   }
+  return nA - nR;
+}
+
+__device__ __forceinline__ bool vocab_apply_incremental(const VocabPtrs& p, int b, const int32_t* src, int a, int* sh) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int V = p.V, W = p.window, cap = p.cap;
+  int32_t* ids = p.ids + (size_t)b * cap;
+  uint32_t* gw = p.wbit + (size_t)b * p.nwords;
+  const uint32_t* gt = p.tbit + (size_t)b * p.nwords;
+  uint32_t* cnt = p.cnt + (size_t)b * V;
+  int32_t* ring = p.ring + (size_t)b * W;
+  // everything that does not depend on the state's scalars is requested first
+  const int n_old = p.n[b], pos = p.pos[b], fill = p.fill[b];
+  const bool ap = tid >= kIncMax && tid < kIncMax + a;        // this thread appends src[tid - kIncMax]
+  int v = -1;
+  if (ap) v = src[tid - kIncMax];
+  int4 q0 = make_int4(INT_MAX, INT_MAX, INT_MAX, INT_MAX);
+  int q0n = INT_MAX;
+  if (4 * tid < cap) q0 = *reinterpret_cast<const int4*>(ids + 4 * tid);   // cap is a multiple of 4
+  if (4 * tid + 4 < cap) q0n = ids[4 * tid + 4];
+  if (n_old + a > cap) return false;
+  int xs[5];
+  inc_mask(0, tid, n_old, q0, q0n, xs);
+
+  int n_evict = fill + a - W;                // a <= W here
+  if (n_evict < 0) n_evict = 0;
+  int oldest = pos - fill;
+  if (oldest < 0) oldest += W;
+  int bad = 0;
+
+  if (tid < 64) {
+    int id = -1;
+    if (ap) {
+      if ((unsigned)v < (unsigned)V) id = v;
+      else bad = 1;
+    } else if (lane < n_evict) {
+      int slot = oldest + lane;
+      if (slot >= W) slot -= W;
+      id = ring[slot];
+    }
+    const bool valid = id >= 0;
+    uint32_t tw = 0u, oldc = 0u;
+    if (valid) {
+      tw = gt[id >> 5];
+      oldc = cnt[id];
+    }
+    // net change of this lane's id over all lanes, and whether an earlier lane holds the same id
+    int total = 0;
+    bool first = true;
+    for (int j = 0; j < n_evict; ++j) {
+      const bool same = valid && __builtin_amdgcn_readlane(id, j) == id;
+      total -= same ? 1 : 0;
+      first = first && !(same && j < lane);
+    }
+    for (int j = kIncMax; j < kIncMax + a; ++j) {
+      const bool same = valid && __builtin_amdgcn_readlane(id, j) == id;
+      total += same ? 1 : 0;
+      first = first && !(same && j < lane);
+    }
+    if (ap) {
+      int slot = pos + (lane - kIncMax);
+      if (slot >= W) slot -= W;
+      ring[slot] = id;                         // the leaving entries are in registers by now; -1 for an id out of range
+    }
+    const bool lead = valid && first;
+    const uint32_t newc = oldc + (uint32_t)total;
+    const uint32_t bit = 1u << (id & 31);
+    if (lead && total != 0) cnt[id] = newc;
+    const bool left = lead && oldc != 0u && newc == 0u, entered = lead && oldc == 0u && newc != 0u;
+    if (left) atomicAnd(&gw[id >> 5], ~bit);   // another lane may own a different bit of the same word
+    if (entered) atomicOr(&gw[id >> 5], bit);
+    const int r = (left && !(tw & bit)) ? id : INT_MAX;
+    const int av = (entered && !(tw & bit)) ? id : INT_MAX;
+    inc_publish(r, av, lane, IncScratch(sh));
+  }
+  __syncthreads();
+  const int dn = inc_patch(ids, cap, n_old, xs, IncScratch(sh));
   if (tid == 0) {
-    p.n[b] = n_old + nA - nR;
+    p.n[b] = n_old + dn;
     int np = pos + a;
     if (np >= W) np -= W;
     p.pos[b] = np;
@@ -577,6 +604,89 @@ __device__ __forceinline__ void fifo_apply_body(const VocabPtrs& p, int b, const
   if (bad) atomicOr(p.err, (int)NANOSPEC_DEV_BAD_ID);
 }
 
+// The queue reading's list patch (appends of at most kIncMax ids, T untouched): the first wavefront finds the
+// new ids -- valid, not members when the call starts, first occurrence in the call, in call order -- pushes them,
+// drops as many of the oldest members as the queue overflows by, and hands the ids that left or entered the
+// active set to the same list patch as the window reading.  The membership bitmap stays in HBM.
+__device__ __forceinline__ bool fifo_apply_incremental(const VocabPtrs& p, int b, const int32_t* src, int a, int* sh) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int V = p.V, cap = p.cap;
+  const int W = p.window < V ? p.window : V;
+  int32_t* ids = p.ids + (size_t)b * cap;
+  uint32_t* gw = p.wbit + (size_t)b * p.nwords;
+  const uint32_t* gt = p.tbit + (size_t)b * p.nwords;
+  int32_t* ring = p.ring + (size_t)b * p.window;
+  const int n_old = p.n[b], pos = p.pos[b], fill = p.fill[b];
+  const bool ap = tid >= kIncMax && tid < kIncMax + a;        // this thread appends src[tid - kIncMax]
+  int v = -1;
+  if (ap) v = src[tid - kIncMax];
+  int4 q0 = make_int4(INT_MAX, INT_MAX, INT_MAX, INT_MAX);
+  int q0n = INT_MAX;
+  if (4 * tid < cap) q0 = *reinterpret_cast<const int4*>(ids + 4 * tid);
+  if (4 * tid + 4 < cap) q0n = ids[4 * tid + 4];
+  if (n_old + a > cap) return false;
+  int xs[5];
+  inc_mask(0, tid, n_old, q0, q0n, xs);
+  int oldest = pos - fill;
+  if (oldest < 0) oldest += W;
+  int bad = 0;
+  const IncScratch sc(sh);
+
+  if (tid < 64) {
+    // lanes 16..31: the appended ids; lanes 0..15: the oldest members, of which the first n_ev leave -- how
+    // many is known only when the new ids have been counted, so all candidates are fetched at once
+    int id = -1;
+    if (ap) {
+      if ((unsigned)v < (unsigned)V) id = v;
+      else bad = 1;
+    } else if (lane < a && lane < fill) {
+      int slot = oldest + lane;
+      if (slot >= W) slot -= W;
+      id = ring[slot];
+    }
+    uint32_t tw = 0u, ww = 0u;
+    if (id >= 0) {
+      tw = gt[id >> 5];
+      if (ap) ww = gw[id >> 5];
+    }
+    const uint32_t bit = 1u << (id & 31);
+    bool isnew = ap && id >= 0 && !(ww & bit);
+    for (int j = kIncMax; j < kIncMax + a; ++j) {
+      const bool same = __builtin_amdgcn_readlane(id, j) == id;
+      isnew = isnew && !(same && j < lane);
+    }
+    const unsigned long long mn = __ballot(isnew);
+    const int nF = __popcll(mn);                             // a <= W: all of them stay
+    int n_ev = fill + nF - W;
+    if (n_ev < 0) n_ev = 0;
+    if (isnew) {
+      int slot = pos + __popcll(mn & ((1ull << lane) - 1ull));
+      if (slot >= W) slot -= W;
+      ring[slot] = id;                                       // the members that leave are in registers by now
+      atomicOr(&gw[id >> 5], bit);
+    }
+    const bool leaves = !ap && lane < n_ev && id >= 0;
+    if (leaves) atomicAnd(&gw[id >> 5], ~bit);
+    const int r = (leaves && !(tw & bit)) ? id : INT_MAX;
+    const int av = (isnew && !(tw & bit)) ? id : INT_MAX;
+    inc_publish(r, av, lane, sc);
+    if (lane == 0) sc.sN[3] = nF;
+  }
+  __syncthreads();
+  const int nF = sc.sN[3];
+  const int dn = inc_patch(ids, cap, n_old, xs, sc);
+  if (tid == 0) {
+    p.n[b] = n_old + dn;
+    int np = pos + nF;
+    if (np >= W) np -= W;
+    p.pos[b] = np;
+    const int nf = fill + nF;
+    p.fill[b] = nf < W ? nf : W;
+  }
+  if (bad) atomicOr(p.err, (int)NANOSPEC_DEV_BAD_ID);
+  return true;
+}
+
 __global__ __launch_bounds__(kVocabThreads) void vocab_fifo_kernel(VocabPtrs p, const int32_t* __restrict__ new_ids,
                                                                    Offsets noff, const int32_t* __restrict__ topk,
                                                                    Offsets toff, int replace_T) {
@@ -587,10 +697,13 @@ __global__ __launch_bounds__(kVocabThreads) void vocab_fifo_kernel(VocabPtrs p, 
   int* sc = reinterpret_cast<int*>(tb + nwords);
   uint32_t* ub = reinterpret_cast<uint32_t*>(sc + 32);
   int32_t* cl = reinterpret_cast<int32_t*>(ub + nwords);
+  const int a = noff.v[b + 1] - noff.v[b];
+  if (!replace_T && a <= kIncMax && a <= p.window && a <= p.V &&
+      fifo_apply_incremental(p, b, new_ids + noff.v[b], a, reinterpret_cast<int*>(lds)))
+    return;
   load_bitmaps(p, b, wb, tb, replace_T);
   for (int i = tid * 4; i < nwords; i += kVocabThreads * 4) *reinterpret_cast<uint4*>(ub + i) = make_uint4(0, 0, 0, 0);
-  fifo_apply_body(p, b, new_ids + noff.v[b], noff.v[b + 1] - noff.v[b], topk + toff.v[b], toff.v[b + 1] - toff.v[b],
-                  replace_T, wb, tb, ub, sc, cl, 0);
+  fifo_apply_body(p, b, new_ids + noff.v[b], a, topk + toff.v[b], toff.v[b + 1] - toff.v[b], replace_T, wb, tb, ub, sc, cl, 0);
 }
 
 // candidate set built on the device, queue reading: distinct valid candidates in ascending order, then one batch

@@ -143,16 +143,18 @@ def test_edge_cases_vocab():
     st.close()
 
 
+@pytest.mark.parametrize("policy", [0, 1])
 @pytest.mark.parametrize("V,W,distinct", [(60000, 20000, 13000), (5000, 4096, 5000), (300, 37, 300), (64, 64, 64)])
-def test_short_appends_patch_the_list(V, W, distinct):
-    """Updates of at most 16 ids with T untouched take the list-patching route: ids below the first and
+def test_short_appends_patch_the_list(V, W, distinct, policy):
+    """Updates of at most 16 ids with T untouched take the list-patching route (both stream policies): ids below the first and
     above the last entry, ids that T holds, ids that leave and come back in one call, duplicates, ids out of
     range, lists of several passes, a list at its capacity (V = 64: the general route takes over) -- the
     active list equals the oracle's after every call, for three sequences with different streams."""
     Bn, tcap = 3, 64
     rng = np.random.default_rng(V + W)
     st = B.State(V, 64, Bn, W, tcap, 4, 8)
-    orc = [oracle.Vocab(V, W) for _ in range(Bn)]
+    B.nanospec_set_stream_policy(st.h, policy)
+    orc = [oracle.FifoVocab(V, W) if policy else oracle.Vocab(V, W) for _ in range(Bn)]
     ctx = [rng.integers(V // 10, V // 10 + distinct * 8 // 10, size=W + 50).astype(np.int32) % V for _ in range(Bn)]
     T = [rng.integers(0, V, size=tcap).astype(np.int32) for _ in range(Bn)]
     f, off = csr(ctx)

@@ -122,15 +122,16 @@ __global__ __launch_bounds__(64 * NW) void head_quad_private_kernel(const uint16
   const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
   const uint16_t* Hb = H + (int64_t)b * M * d;
 
-  // FAST (chosen by the launcher): d is a whole number of K-iterations and M == 4*MT, so no load needs a
-  // bounds test and every address is a per-row base plus a compile-time offset -- two instructions per
+  // FAST (chosen by the launcher): d is a whole number of K-iterations, so no load needs a bounds test
+  // (hidden rows past M are clamped; their products are never stored) and every address is a per-row base
+  // plus a compile-time offset -- two instructions per
   // load instead of a branch and a dozen (the generic form spends ~600 instructions per wavefront on its
   // 32 hidden-row loads before the first weight load is issued).
   auto load_h = [&](int kb, u32x4(&hv)[MT][KS]) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       const int m = mt * 4 + orow;
-      const uint16_t* hp = Hb + (int64_t)m * d + coff + kb;
+      const uint16_t* hp = Hb + (int64_t)(m < M ? m : M - 1) * d + coff + kb;   // a row past M is a copy, never stored
 #pragma unroll
       for (int t = 0; t < KS; ++t) {
         const int c = kb + coff + t * 128;
@@ -234,7 +235,7 @@ static hipError_t run_quad_private(const uint16_t* W, const uint16_t* H, const i
   const int tiles = (cap_rows + 4 * RT - 1) / (4 * RT);
   const int seq_first = batch > 1 && tiles <= 65535;
   const dim3 grid = seq_first ? dim3(batch, tiles, 1) : dim3(tiles, 1, batch);
-  if (d % (NW * 128 * KS) == 0 && M == 4 * MT)
+  if (d % (NW * 128 * KS) == 0)
     head_quad_private_kernel<RT, MT, KS, NW, true><<<grid, 64 * NW, 0, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride,
                                                                             logits, seq_first);
   else
@@ -419,19 +420,14 @@ static hipError_t run_quad(const uint16_t* W, const uint16_t* H, const int32_t* 
   if (once.needed(&dev)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_quad_kernel<NRG, RT, MT, KS, true>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_quad_kernel<NRG, RT, MT, KS, false>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (e != hipSuccess) return e;
     once.mark(dev);
   }
   const int tiles = (cap_rows + ROWS - 1) / ROWS;
   const int seq_first = batch > 1 && tiles <= 65535;
   const dim3 grid = seq_first ? dim3(batch, tiles, 1) : dim3(tiles, 1, batch);
-  if (d <= 512 * KS)
-    head_quad_kernel<NRG, RT, MT, KS, true><<<grid, 256 * NRG, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits, seq_first);
-  else
-    head_quad_kernel<NRG, RT, MT, KS, false><<<grid, 256 * NRG, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits, seq_first);
+  if (d > 512 * KS) return hipErrorInvalidValue;          // callers send longer rows to the K-loop kernel
+  head_quad_kernel<NRG, RT, MT, KS, true><<<grid, 256 * NRG, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits, seq_first);
   return hipGetLastError();
 }
 
@@ -471,8 +467,9 @@ static hipError_t run_quad_auto(const uint16_t* W, const uint16_t* H, const int3
 //   LOOPK = false: split-K -- slice = blockIdx.y, partial products go to that slice's plane and
 //                  head_splitk_reduce_kernel adds the planes in slice order (few rows: the rows
 //                  alone cannot fill the chip; deterministic because the order is fixed).
-//   FAST (chosen by the launcher): M == 16*MT and d a whole number of slices, so no load needs a bounds
-//   test; rows past the end read row 0 instead of being skipped, the row count arrives on the vector
+//   FAST (chosen by the launcher): d a whole number of slices, so no load needs a bounds test; hidden
+//   rows past M are clamped and rows past the end read row 0 instead of being skipped (neither is ever
+//   stored), the row count arrives on the vector
 //   path behind the ids, and every address is a base plus a lane offset.  The generic form spends ~25
 //   instructions and a branch on each of its 32 loads per slice (~860 instructions before the last weight
 //   load of the first slice is issued) and, because of the branches, waits for all hidden-row loads
@@ -503,9 +500,12 @@ __global__ __launch_bounds__(256) void head_tile64_kernel(const uint16_t* __rest
   auto load_slice = [&](int sl) {
     if constexpr (FAST) {
       const uint32_t cb = (uint32_t)(sl * 512 + lane * 8) * 2u;            // byte offset inside a row
-      const char* hp = reinterpret_cast<const char*>(H + ((int64_t)b * M + w * 16) * d) + cb;
+      const char* hp = reinterpret_cast<const char*>(H + (int64_t)b * M * d) + cb;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) hv[r] = *reinterpret_cast<const u32x4*>(hp + (int64_t)r * d * 2);
+      for (int r = 0; r < 16; ++r) {
+        const int m = w * 16 + r;                                           // a hidden row past M is a copy, never stored
+        hv[r] = *reinterpret_cast<const u32x4*>(hp + (int64_t)(m < M ? m : M - 1) * d * 2);
+      }
       __builtin_amdgcn_sched_barrier(0);                                  // the hidden-row loads go out before the ids are waited for
       n = __builtin_amdgcn_readfirstlane(nv);
       // lane r (mod 16) works out the byte offset of row r once; the wavefront then needs two readlanes,
@@ -626,7 +626,7 @@ static hipError_t run_splitk(const uint16_t* W, const uint16_t* H, const int32_t
                              int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride, float* logits,
                              float* partial, int S, hipStream_t s) {
   constexpr int LDS = 4 * 16 * (1024 + 16);
-  const bool fast = M == 16 * MT && d % 512 == 0;
+  const bool fast = d % 512 == 0;
   hipError_t e = fast ? tile64_configure<MT, false, true>() : tile64_configure<MT, false, false>();
   if (e != hipSuccess) return e;
   const dim3 grid((cap_rows + 63) / 64, S, batch);
@@ -644,7 +644,7 @@ static hipError_t run_tile64(const uint16_t* W, const uint16_t* H, const int32_t
                              int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride,
                              float* logits, hipStream_t s) {
   constexpr int LDS = 4 * 16 * (1024 + 16);
-  const bool fast = M == 16 * MT && d % 512 == 0;
+  const bool fast = d % 512 == 0;
   hipError_t e = fast ? tile64_configure<MT, true, true>() : tile64_configure<MT, true, false>();
   if (e != hipSuccess) return e;
   const dim3 grid((cap_rows + 63) / 64, 1, batch);

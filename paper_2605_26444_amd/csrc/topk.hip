@@ -21,7 +21,9 @@
 // Measured and not kept: handing out the LDS slots with one atomic counter and breaking ties by position;
 // splitting the valid runs evenly over the wavefronts (the layout then depends on n: c2 4.2 against
 // 4.1 us, c3 5.0 against 4.6); fetching every lane's 16 ids beside its logits so that the winners' ids
-// need no second round trip (4.3-4.4 us on c2).
+// need no second round trip (4.3-4.4 us on c2); a single-pass threshold -- the smallest maximum of the filled
+// 16-lane rows, no rounds -- which lets so many more candidates through that nothing is gained at 3k
+// elements (3.74 against 3.72 us) and the 8k-element case falls back to the rounds (12.0 against 6.6 us).
 //
 // LSE variants (Sec. 4.2: the draft distribution is the softmax renormalised over the active set):
 // the same selection, with the values written as log-probabilities z - log(sum_i exp z_i), i over the

@@ -161,12 +161,27 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
   const bool fin = FINAL || n <= NW * 64 * EPT;           // uniform over the grid row
   if (!FINAL && fin && c != 0) return;
   float lse = 0.f;                                        // log sum exp of the row (LSE && fin)
+  __shared__ float s_thr[NW];
+  __shared__ float s_wmax[NW];
+  __shared__ float s_sum[NW];
+  __shared__ int s_cnt[NW];
+  // A wavefront that holds nothing of the row leaves at once (a barrier waits only for the wavefronts that
+  // are still running): with sixteen wavefronts on four SIMDs every instruction of an idle one delays the
+  // others.  It first leaves the neutral entries the others will read; the first four always stay, for the
+  // per-thread chores below (up to kCandMax candidates, k padding slots).
+  const int nwl = nwa > 4 ? nwa : (NW < 4 ? NW : 4);      // wavefronts that stay, 0 .. nwl-1
+  if (wave >= nwl) {
+    if (lane == 0) {
+      s_cnt[wave] = 0;
+      s_wmax[wave] = -INFINITY;
+      s_sum[wave] = 0.f;
+    }
+    if (lane < k) s_val[wave * k + lane] = -INFINITY;
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // the entries are in LDS before this wavefront is gone
+    return;
+  }
   // ---- fast path: threshold from lane maxima, compaction, ranking
   {
-    __shared__ float s_thr[NW];
-    __shared__ float s_wmax[NW];
-    __shared__ float s_sum[NW];
-    __shared__ int s_cnt[NW];
     __shared__ __attribute__((aligned(16))) float s_cv[kCandMax + 4];
     __shared__ int s_cp[kCandMax];
     float ml = v[0];
@@ -260,7 +275,7 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
       // (padded to a power of two), so a few dozen candidates are ranked in one sweep of the workgroup.
       const int lg = C <= 1 ? 0 : 32 - __clz(C - 1);
       const int items = ((C + 3) >> 2) << lg;
-      for (int w = tid; w < items; w += 64 * NW) {
+      for (int w = tid; w < items; w += 64 * nwl) {
         const int t = w & ((1 << lg) - 1), q = (w >> lg) * 4;
         if (t < C) {
           const float val = s_cv[t];
@@ -308,7 +323,7 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
           ++off;
         }
       __syncthreads();
-      for (int t = tid; t < (C > k ? C : k); t += 64 * NW) {
+      for (int t = tid; t < (C > k ? C : k); t += 64 * nwl) {
         int64_t o;
         int pos = -1;
         float val = -INFINITY;

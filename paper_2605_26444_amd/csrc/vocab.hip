@@ -320,7 +320,7 @@ __device__ __forceinline__ int inc_patch(int32_t* ids, int cap, int n_old, int (
       }
       const int j0 = pass * kIncPass + 4 * tid;
       const bool head = j0 == 0;
-      if (xs[4] > lowest || head) {            // entries below every change stay where they are
+      if ((xs[0] != INT_MAX && xs[4] > lowest) || head) {   // entries below every change stay where they are; past the end there are none
         // changes below the thread's first entry shift all four alike; a change inside its span (rare: at
         // most one thread per change) is worked out entry by entry on top of that
         int m0 = 0, inside = 0;

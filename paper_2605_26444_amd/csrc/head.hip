@@ -467,14 +467,14 @@ static hipError_t run_quad_auto(const uint16_t* W, const uint16_t* H, const int3
 //   LOOPK = false: split-K -- slice = blockIdx.y, partial products go to that slice's plane and
 //                  head_splitk_reduce_kernel adds the planes in slice order (few rows: the rows
 //                  alone cannot fill the chip; deterministic because the order is fixed).
-//   FAST (chosen by the launcher): d a whole number of slices, so no load needs a bounds test; hidden
-//   rows past M are clamped and rows past the end read row 0 instead of being skipped (neither is ever
-//   stored), the row count arrives on the vector
+//   FAST 1 / 2 (chosen by the launcher): d a whole number of slices, so no load needs a bounds test; hidden
+//   rows past M are clamped (1) or do not exist (2: M == 16*MT) and rows past the end read row 0 instead
+//   of being skipped (neither is ever stored), the row count arrives on the vector
 //   path behind the ids, and every address is a base plus a lane offset.  The generic form spends ~25
 //   instructions and a branch on each of its 32 loads per slice (~860 instructions before the last weight
 //   load of the first slice is issued) and, because of the branches, waits for all hidden-row loads
 //   before it issues the first weight load.
-template <int MT, bool LOOPK, bool FAST>
+template <int MT, bool LOOPK, int FAST>
 __global__ __launch_bounds__(256) void head_tile64_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
                                                           const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
                                                           int n_fixed, int V, int M, int d, int64_t ld, int64_t ids_stride,
@@ -498,13 +498,19 @@ __global__ __launch_bounds__(256) void head_tile64_kernel(const uint16_t* __rest
   u32x4 hv[16], wv[16];
   int n = nv;
   auto load_slice = [&](int sl) {
-    if constexpr (FAST) {
+    if constexpr (FAST != 0) {
       const uint32_t cb = (uint32_t)(sl * 512 + lane * 8) * 2u;            // byte offset inside a row
       const char* hp = reinterpret_cast<const char*>(H + (int64_t)b * M * d) + cb;
+      if constexpr (FAST == 2) {                                          // M == 16*MT: constant strides
+        const char* hw = hp + (int64_t)w * 16 * d * 2;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = w * 16 + r;                                           // a hidden row past M is a copy, never stored
-        hv[r] = *reinterpret_cast<const u32x4*>(hp + (int64_t)(m < M ? m : M - 1) * d * 2);
+        for (int r = 0; r < 16; ++r) hv[r] = *reinterpret_cast<const u32x4*>(hw + (int64_t)r * d * 2);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = w * 16 + r;                                         // a hidden row past M is a copy, never stored
+          hv[r] = *reinterpret_cast<const u32x4*>(hp + (int64_t)(m < M ? m : M - 1) * d * 2);
+        }
       }
       __builtin_amdgcn_sched_barrier(0);                                  // the hidden-row loads go out before the ids are waited for
       n = __builtin_amdgcn_readfirstlane(nv);
@@ -608,7 +614,7 @@ __global__ __launch_bounds__(256) void head_splitk_reduce_kernel(const float* __
   *reinterpret_cast<f32x4*>(logits + ((int64_t)b * M + m) * ld + j) = s;
 }
 
-template <int MT, bool LOOPK, bool FAST>
+template <int MT, bool LOOPK, int FAST>
 static hipError_t tile64_configure() {
   static PerDeviceOnce once;
   int dev;
@@ -626,12 +632,13 @@ static hipError_t run_splitk(const uint16_t* W, const uint16_t* H, const int32_t
                              int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride, float* logits,
                              float* partial, int S, hipStream_t s) {
   constexpr int LDS = 4 * 16 * (1024 + 16);
-  const bool fast = d % 512 == 0;
-  hipError_t e = fast ? tile64_configure<MT, false, true>() : tile64_configure<MT, false, false>();
+  const int fast = d % 512 != 0 ? 0 : (M == 16 * MT ? 2 : 1);
+  hipError_t e = fast == 2 ? tile64_configure<MT, false, 2>() : fast == 1 ? tile64_configure<MT, false, 1>() : tile64_configure<MT, false, 0>();
   if (e != hipSuccess) return e;
   const dim3 grid((cap_rows + 63) / 64, S, batch);
-  if (fast) head_tile64_kernel<MT, false, true><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial);
-  else head_tile64_kernel<MT, false, false><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial);
+  if (fast == 2) head_tile64_kernel<MT, false, 2><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial);
+  else if (fast == 1) head_tile64_kernel<MT, false, 1><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial);
+  else head_tile64_kernel<MT, false, 0><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   head_splitk_reduce_kernel<<<dim3((cap_rows / 4 + 255) / 256, M, batch), 256, 0, s>>>(partial, n_dev, S, M, cap_rows, ld,
@@ -644,12 +651,13 @@ static hipError_t run_tile64(const uint16_t* W, const uint16_t* H, const int32_t
                              int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride,
                              float* logits, hipStream_t s) {
   constexpr int LDS = 4 * 16 * (1024 + 16);
-  const bool fast = d % 512 == 0;
-  hipError_t e = fast ? tile64_configure<MT, true, true>() : tile64_configure<MT, true, false>();
+  const int fast = d % 512 != 0 ? 0 : (M == 16 * MT ? 2 : 1);
+  hipError_t e = fast == 2 ? tile64_configure<MT, true, 2>() : fast == 1 ? tile64_configure<MT, true, 1>() : tile64_configure<MT, true, 0>();
   if (e != hipSuccess) return e;
   const dim3 grid((cap_rows + 63) / 64, 1, batch);
-  if (fast) head_tile64_kernel<MT, true, true><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
-  else head_tile64_kernel<MT, true, false><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
+  if (fast == 2) head_tile64_kernel<MT, true, 2><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
+  else if (fast == 1) head_tile64_kernel<MT, true, 1><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
+  else head_tile64_kernel<MT, true, 0><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
   return hipGetLastError();
 }
 

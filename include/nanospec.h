@@ -130,8 +130,10 @@ NANOSPEC_API nanospec_status nanospec_vocab_init(nanospec_state* st, const int32
                                     const int32_t* d_topk_ids, const int32_t* h_topk_off, void* hip_stream);
 
 /* Stream update, Eq. 3 followed by Eq. 4: append new_ids[h_new_off[b] .. h_new_off[b+1]) to the
- * stream of sequence b (zero ids is legal), evict what leaves the window, and rebuild the
- * ascending active list and its count -- one launch for the whole batch.  If d_topk_ids is not
+ * stream of sequence b (zero ids is legal), evict what leaves the window, and bring the
+ * ascending active list and its count up to date -- one launch for the whole batch (appends of
+ * at most 16 ids that leave T alone patch the list in place, anything else rebuilds it; the
+ * result is the same list either way).  If d_topk_ids is not
  * NULL (or h_topk_off is not NULL with all-empty ranges) the set T of every sequence is replaced
  * wholesale; pass both NULL to keep T.  Same argument rules and errors as nanospec_vocab_init.
  * Asynchronous. */

@@ -468,7 +468,7 @@ static hipError_t run_quad_auto(const uint16_t* W, const uint16_t* H, const int3
 //                  head_splitk_reduce_kernel adds the planes in slice order (few rows: the rows
 //                  alone cannot fill the chip; deterministic because the order is fixed).
 //   FAST 1 / 2 (chosen by the launcher): d a whole number of slices, so no load needs a bounds test; hidden
-//   rows past M are clamped (1) or do not exist (2: M == 16*MT) and rows past the end read row 0 instead
+//   rows past M are clamped (1) or do not occur (2: M == 64, sixteen per wavefront) and rows past the end read row 0 instead
 //   of being skipped (neither is ever stored), the row count arrives on the vector
 //   path behind the ids, and every address is a base plus a lane offset.  The generic form spends ~25
 //   instructions and a branch on each of its 32 loads per slice (~860 instructions before the last weight
@@ -501,7 +501,7 @@ __global__ __launch_bounds__(256) void head_tile64_kernel(const uint16_t* __rest
     if constexpr (FAST != 0) {
       const uint32_t cb = (uint32_t)(sl * 512 + lane * 8) * 2u;            // byte offset inside a row
       const char* hp = reinterpret_cast<const char*>(H + (int64_t)b * M * d) + cb;
-      if constexpr (FAST == 2) {                                          // M == 16*MT: constant strides
+      if constexpr (FAST == 2) {                                          // M == 64: all four wavefronts' hidden rows exist, constant strides
         const char* hw = hp + (int64_t)w * 16 * d * 2;
 #pragma unroll
         for (int r = 0; r < 16; ++r) hv[r] = *reinterpret_cast<const u32x4*>(hw + (int64_t)r * d * 2);
@@ -632,7 +632,7 @@ static hipError_t run_splitk(const uint16_t* W, const uint16_t* H, const int32_t
                              int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride, float* logits,
                              float* partial, int S, hipStream_t s) {
   constexpr int LDS = 4 * 16 * (1024 + 16);
-  const int fast = d % 512 != 0 ? 0 : (M == 16 * MT ? 2 : 1);
+  const int fast = d % 512 != 0 ? 0 : (M == 64 ? 2 : 1);   // 2: every wavefront's sixteen hidden rows exist
   hipError_t e = fast == 2 ? tile64_configure<MT, false, 2>() : fast == 1 ? tile64_configure<MT, false, 1>() : tile64_configure<MT, false, 0>();
   if (e != hipSuccess) return e;
   const dim3 grid((cap_rows + 63) / 64, S, batch);
@@ -651,7 +651,7 @@ static hipError_t run_tile64(const uint16_t* W, const uint16_t* H, const int32_t
                              int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride,
                              float* logits, hipStream_t s) {
   constexpr int LDS = 4 * 16 * (1024 + 16);
-  const int fast = d % 512 != 0 ? 0 : (M == 16 * MT ? 2 : 1);
+  const int fast = d % 512 != 0 ? 0 : (M == 64 ? 2 : 1);   // 2: every wavefront's sixteen hidden rows exist
   hipError_t e = fast == 2 ? tile64_configure<MT, true, 2>() : fast == 1 ? tile64_configure<MT, true, 1>() : tile64_configure<MT, true, 0>();
   if (e != hipSuccess) return e;
   const dim3 grid((cap_rows + 63) / 64, 1, batch);

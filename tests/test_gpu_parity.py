@@ -441,6 +441,10 @@ def test_step_recorded_in_hip_graph_replays_correctly():
     (520, 1, 37, 1), (520, 3, 300, 2), (1032, 5, 1500, 1), (3592, 8, 3001, 1), (4096, 9, 777, 1), (1032, 13, 2900, 3),
     (520, 16, 9000, 1), (1032, 17, 1000, 1), (3592, 33, 1234, 1), (1032, 64, 17000, 1), (520, 70, 500, 1), (520, 70, 200, 2),
     (4096, 16, 3000, 1), (3592, 12, 1500, 1), (8200, 16, 2000, 1), (8200, 8, 9000, 1), (1032, 8, 3100, 3), (4104, 6, 200, 1),
+    # the variants without bounds tests (d a whole number of K-iterations / slices), with hidden rows that fill the
+    # last tile and with hidden rows that do not; the last sequence's hidden rows end the H buffer
+    (8192, 32, 70, 2), (1024, 17, 1000, 1), (2048, 48, 300, 2), (1024, 64, 2000, 1), (512, 64, 17000, 1), (512, 40, 17000, 1),
+    (8192, 12, 1300, 1), (8192, 10, 500, 2), (6144, 16, 9000, 1), (4096, 3, 100, 1),
 ])
 def test_head_shapes_against_oracle(d, M, n_ctx, batch):
     """every head kernel and its ragged tails: row counts that are not multiples of the tile, hidden sizes that

@@ -197,7 +197,7 @@ __global__ __launch_bounds__(64 * NW) void topk_select_kernel(const float* __res
         const float ref = wmax == -INFINITY ? 0.f : wmax;   // nothing valid here: every term is exp(-inf) = 0
         float se = 0.f;
 #pragma unroll
-        for (int e = 0; e < EPT; ++e) se += expf(v[e] - ref);
+        for (int e = 0; e < EPT; ++e) se += __expf(v[e] - ref);
         wsum = wave_add(se);
       }
       const unsigned long long ball = __ballot(x == thr);

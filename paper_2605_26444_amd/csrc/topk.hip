@@ -24,6 +24,8 @@
 // need no second round trip (4.3-4.4 us on c2); a single-pass threshold -- the smallest maximum of the filled
 // 16-lane rows, no rounds -- which lets so many more candidates through that nothing is gained at 3k
 // elements (3.74 against 3.72 us) and the 8k-element case falls back to the rounds (12.0 against 6.6 us).
+// Half-wavefronts as voters (twice the voters, half the rounds, two thresholds per round) helped only
+// the unlucky lengths with a single voting wavefront (1.3k elements: 4.0 against 4.3 us) and cost 0.1-1 us elsewhere.
 //
 // LSE variants (Sec. 4.2: the draft distribution is the softmax renormalised over the active set):
 // the same selection, with the values written as log-probabilities z - log(sum_i exp z_i), i over the

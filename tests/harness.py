@@ -10,6 +10,9 @@ from paper_2605_26444_amd import binding as B
 from paper_2605_26444_amd import synth
 
 ATOL, RTOL = 2e-3, 1e-3          # logit tolerance fixed by the benchmark spec (fp32 accumulation)
+# two fp32 sums of the same d exact products differ by at most ~2*d*2^-24*sum|w h| (~5e-6 at d = 8192, |logit| ~ 2);
+# only ranks whose exact logits are closer than this can come out in the other order
+SWAP_TOL = 2e-5
 
 _W_CACHE: dict = {}
 
@@ -53,7 +56,7 @@ def assert_logits_close(g, o64, o32=None, what=""):
     return float(err.max())
 
 
-def check_topk(g_ids, g_vals, g_logits_row, o32_row, active, k, stats, what=""):
+def check_topk(g_ids, g_vals, g_logits_row, o32_row, active, k, stats, what="", o64_row=None):
     """two-level check of one (sequence, hidden row)."""
     # level 1 (strict): the oracle's selection applied to the GPU's own logits, ties included
     oi, ov = oracle.topk(g_logits_row, active, k)
@@ -76,9 +79,16 @@ def check_topk(g_ids, g_vals, g_logits_row, o32_row, active, k, stats, what=""):
         stats["rows_checked_e2e"] = stats.get("rows_checked_e2e", 0) + 1
     else:
         stats["rows_near_tie"] = stats.get("rows_near_tie", 0) + 1
-        # with accumulation noise ~1e-6 the ids are in practice identical even there: report if not
+        # a near tie may legitimately come out in the other order: the two sides add the same exact products in a
+        # different order (observed |difference| <= 2e-6).  Where the ids differ the GPU's choice must still be a
+        # valid one: at every rank its id's exact (fp64) logit lies within SWAP_TOL of the oracle's id's.
         if not np.array_equal(g_ids[:m], ei[:m]):
             stats["rows_near_tie_differ"] = stats.get("rows_near_tie_differ", 0) + 1
+            if o64_row is not None:
+                where = {int(t): j for j, t in enumerate(active)}
+                ge = np.array([o64_row[where[int(t)]] for t in g_ids[:m]])
+                oe = np.array([o64_row[where[int(t)]] for t in ei[:m]])
+                assert np.all(np.abs(ge - oe) <= SWAP_TOL), f"{what}: ids differ beyond a near tie ({np.abs(ge - oe).max():.3e})"
 
 
 def run_workload(cfg, target=None, check_steps=None, M=None, k=None, W_bits=None, dW=None):
@@ -128,7 +138,8 @@ def run_workload(cfg, target=None, check_steps=None, M=None, k=None, W_bits=None
             e = assert_logits_close(gl[b, :, :n], o64, o32, f"step {step} seq {b}")
             stats["max_err"] = max(stats["max_err"], e)
             for m in range(M):
-                check_topk(gi[b, m], gv[b, m], gl[b, m, :n], o32[m], act[b], k, stats, f"step {step} seq {b} row {m}")
+                check_topk(gi[b, m], gv[b, m], gl[b, m, :n], o32[m], act[b], k, stats, f"step {step} seq {b} row {m}",
+                           o64_row=o64[m])
         stats["steps_checked"] += 1
 
     compare(-1, -1 in check_steps or 0 in check_steps)
@@ -145,4 +156,7 @@ def run_workload(cfg, target=None, check_steps=None, M=None, k=None, W_bits=None
         compare(s, s in check_steps)
     assert B.nanospec_last_device_error(st.h) == 0
     st.close()
+    # rows whose near ties came out in the other order (each was checked to be a valid order above): a handful
+    # at most -- more would point at a real difference
+    assert stats.get("rows_near_tie_differ", 0) <= max(1, stats.get("rows_near_tie", 0) // 500), stats
     return stats

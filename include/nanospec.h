@@ -209,6 +209,20 @@ NANOSPEC_API nanospec_status nanospec_dense_topk(const float* d_logits, int32_t 
                                     int32_t* d_out_ids, float* d_out_vals, void* d_workspace,
                                     int64_t workspace_bytes, void* hip_stream);
 
+/* The same selection for callers that cannot allocate device memory -- code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc: no workspace argument; the per-chunk candidates go to a
+ * fixed 4 MiB device array inside the library (one per GPU, held until the process ends, its address looked
+ * up on the first call on each device).  The call allocates and frees nothing.  Output as
+ * nanospec_dense_topk, bit for bit.  Every call on a GPU shares that GPU's array: calls that overlap on one
+ * GPU (two streams, two threads) race and must be serialised by the caller; calls in stream order need no
+ * clearing in between.
+ * Errors: EINVAL (as nanospec_dense_topk), ECAPACITY (nanospec_dense_topk_workspace(V, M_total, k) above
+ * nanospec_dense_topk_static_limit() = 4 MiB, e.g. more than 5957 rows at V = 128256, k = 10), EHIP.
+ * Asynchronous. */
+NANOSPEC_API int64_t nanospec_dense_topk_static_limit(void);
+NANOSPEC_API nanospec_status nanospec_dense_topk_static(const float* d_logits, int32_t V, int32_t M_total, int32_t k,
+                                                        int32_t* d_out_ids, float* d_out_vals, void* hip_stream);
+
 /* Measurement aids, not part of the method: read-only kernels that move the bytes the head moves and
  * compute nothing, to measure what one launch of that size and access pattern can reach on the chip.
  *   nanospec_calib_stream_read : reads d_buf[0, bytes) once, contiguously (bytes a multiple of 16).

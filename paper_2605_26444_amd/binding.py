@@ -24,6 +24,7 @@ EXPORTS = [
     "nanospec_status_string", "nanospec_state_layout", "nanospec_create", "nanospec_destroy",
     "nanospec_set_stream_policy", "nanospec_vocab_init", "nanospec_vocab_update", "nanospec_vocab_append_unique", "nanospec_vocab_view", "nanospec_sparse_head",
     "nanospec_topk_remap", "nanospec_topk_logprob_remap", "nanospec_dense_head", "nanospec_dense_topk_workspace", "nanospec_dense_topk",
+    "nanospec_dense_topk_static_limit", "nanospec_dense_topk_static",
     "nanospec_calib_stream_read", "nanospec_calib_gather_read", "nanospec_last_device_error",
 ]
 
@@ -72,9 +73,12 @@ def lib() -> C.CDLL:
         L.nanospec_dense_topk_workspace.restype = i64
         L.nanospec_dense_topk_workspace.argtypes = [i32, i32, i32]
         L.nanospec_dense_topk.argtypes = [vp, i32, i32, i32, vp, vp, vp, i64, vp]
+        L.nanospec_dense_topk_static_limit.restype = i64
+        L.nanospec_dense_topk_static_limit.argtypes = []
+        L.nanospec_dense_topk_static.argtypes = [vp, i32, i32, i32, vp, vp, vp]
         L.nanospec_last_device_error.argtypes = [vp, i32p, vp]
         for name in EXPORTS:
-            if name not in ("nanospec_status_string", "nanospec_dense_topk_workspace"):
+            if name not in ("nanospec_status_string", "nanospec_dense_topk_workspace", "nanospec_dense_topk_static_limit"):
                 getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -192,6 +196,15 @@ def nanospec_dense_topk_workspace(V, M_total, k) -> int:
 def nanospec_dense_topk(d_logits, V, M_total, k, d_out_ids, d_out_vals, d_workspace, workspace_bytes, stream=None):
     _check(lib().nanospec_dense_topk(_ptr(d_logits), V, M_total, k, _ptr(d_out_ids), _ptr(d_out_vals), _ptr(d_workspace),
                                      workspace_bytes, _stream(stream)), "nanospec_dense_topk")
+
+
+def nanospec_dense_topk_static_limit() -> int:
+    return int(lib().nanospec_dense_topk_static_limit())
+
+
+def nanospec_dense_topk_static(d_logits, V, M_total, k, d_out_ids, d_out_vals, stream=None):
+    _check(lib().nanospec_dense_topk_static(_ptr(d_logits), V, M_total, k, _ptr(d_out_ids), _ptr(d_out_vals),
+                                            _stream(stream)), "nanospec_dense_topk_static")
 
 
 def nanospec_last_device_error(st, stream=None) -> int:

@@ -1,4 +1,5 @@
 // C ABI of libnanospec: argument checking, state allocation, kernel dispatch.
+#include <mutex>
 #include <new>
 
 #include "common.h"
@@ -56,6 +57,24 @@ nanospec_status offsets_to_arg(const int32_t* h_off, int batch, Offsets* out, in
     if (len > 0) *any = true;
   }
   return NANOSPEC_OK;
+}
+
+// Per-device, once: raise the dynamic-LDS limit of every kernel that needs it (a property of the function on a
+// device, not of a state).  Done at nanospec_create and at the first stateless head call on a device.
+std::mutex g_cfg_mu;
+bool g_cfg_done[64] = {};
+
+hipError_t ensure_device_configured() {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_cfg_mu);
+  if (g_cfg_done[dev]) return hipSuccess;
+  e = head_configure_device();
+  if (e == hipSuccess) e = vocab_configure_device();
+  if (e == hipSuccess) g_cfg_done[dev] = true;
+  return e;
 }
 
 // The state's memory and its kernels belong to the device that was current at nanospec_create: a call made
@@ -150,7 +169,7 @@ nanospec_status nanospec_create(nanospec_state** out, int32_t V, int32_t d, int3
   st->partial = reinterpret_cast<float*>(take(st->partial_bytes));
   st->topk_ws_bytes = topk_workspace_bytes(L.capacity, batch * m_cap, k_cap);
   st->topk_ws = take(st->topk_ws_bytes);
-  if (p - st->base > L.total_bytes || vocab_configure(st) != hipSuccess || hipMemset(vp.err, 0, 4) != hipSuccess ||
+  if (p - st->base > L.total_bytes || ensure_device_configured() != hipSuccess || vocab_configure(st) != hipSuccess || hipMemset(vp.err, 0, 4) != hipSuccess ||
       launch_vocab_clear(st, nullptr) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
     (void)hipGetLastError();
     (void)hipHostFree(st->h_err_pinned);
@@ -236,6 +255,7 @@ nanospec_status nanospec_topk_logprob_remap(nanospec_state* st, const float* d_l
 nanospec_status nanospec_dense_head(const void* d_W_bf16, const void* d_H_bf16, int32_t V, int32_t d, int32_t M_total,
                                     float* d_logits, void* hip_stream) {
   if (!d_W_bf16 || !d_H_bf16 || !d_logits || V < 1 || d < 8 || d % 8 != 0 || M_total < 1) return NANOSPEC_EINVAL;
+  if (ensure_device_configured() != hipSuccess) return NANOSPEC_EHIP;   // a flag test after the first call on the device
   hipError_t e = launch_head(d_W_bf16, d_H_bf16, nullptr, nullptr, V, V, V, 1, M_total, d, V, 0, d_logits, nullptr, 0,
                              static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;

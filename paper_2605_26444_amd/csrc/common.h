@@ -54,10 +54,12 @@ hipError_t launch_vocab_clear(const nanospec_state* st, hipStream_t s);
 hipError_t launch_vocab_apply(const nanospec_state* st, const int32_t* d_new, const Offsets& noff,
                               const int32_t* d_topk, const Offsets& toff, int replace_T, hipStream_t s);
 hipError_t vocab_configure(nanospec_state* st);
+hipError_t vocab_configure_device();
 hipError_t launch_vocab_append_unique(const nanospec_state* st, const int32_t* d_cand, int per_seq, int64_t stride,
                                       hipStream_t s);
 
 // head.hip
+hipError_t head_configure_device();
 // logits[b][m][j] for j < n_b (n read on the device).  ids == nullptr: identity list of n_fixed rows.
 hipError_t launch_head(const void* W, const void* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
                        int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld_logits,

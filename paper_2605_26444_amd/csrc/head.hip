@@ -67,22 +67,6 @@ __global__ __launch_bounds__(256) void head_generic_kernel(const uint16_t* __res
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// The dynamic-LDS limit of a kernel is a per-device attribute: remember per device whether it has been
-// raised (one flag array per kernel instantiation).  Returns true when the current device still needs it.
-struct PerDeviceOnce {
-  bool done[64] = {};
-  bool needed(int* dev) {
-    if (hipGetDevice(dev) != hipSuccess || *dev < 0 || *dev >= 64) {
-      *dev = -1;
-      return true;
-    }
-    return !done[*dev];
-  }
-  void mark(int dev) {
-    if (dev >= 0) done[dev] = true;
-  }
-};
-
 // sum over the four lanes of a quad, in every lane of it (DPP quad_perm: neighbours 1 apart, then 2 apart)
 __device__ __forceinline__ float quad_sum(float x) {
   x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xf, 0xf, true));   // quad_perm:[1,0,3,2]
@@ -415,14 +399,6 @@ static hipError_t run_quad(const uint16_t* W, const uint16_t* H, const int32_t* 
                            float* logits, hipStream_t s) {
   constexpr int ROWS = 4 * RT * NRG;
   constexpr int LDS = 4 * MT * KS * 1024 + 4 * NRG * (RT * MT * 16) * 4;
-  static PerDeviceOnce once;
-  int dev;
-  if (once.needed(&dev)) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_quad_kernel<NRG, RT, MT, KS, true>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-    if (e != hipSuccess) return e;
-    once.mark(dev);
-  }
   const int tiles = (cap_rows + ROWS - 1) / ROWS;
   const int seq_first = batch > 1 && tiles <= 65535;
   const dim3 grid = seq_first ? dim3(batch, tiles, 1) : dim3(tiles, 1, batch);
@@ -618,27 +594,13 @@ __global__ __launch_bounds__(256) void head_splitk_reduce_kernel(const float* __
   *reinterpret_cast<f32x4*>(logits + ((int64_t)b * M + m) * ld + j) = s;
 }
 
-template <int MT, bool LOOPK, int FAST>
-static hipError_t tile64_configure() {
-  static PerDeviceOnce once;
-  int dev;
-  if (once.needed(&dev)) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_tile64_kernel<MT, LOOPK, FAST>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 16 * (1024 + kTilePad));
-    if (e != hipSuccess) return e;
-    once.mark(dev);
-  }
-  return hipSuccess;
-}
-
 template <int MT>
 static hipError_t run_splitk(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t cap_rows,
                              int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride, float* logits,
                              float* partial, int S, hipStream_t s) {
   constexpr int LDS = 4 * 16 * (1024 + kTilePad);
   const int fast = d % 512 != 0 ? 0 : (M == 64 ? 2 : 1);   // 2: every wavefront's sixteen hidden rows exist
-  hipError_t e = fast == 2 ? tile64_configure<MT, false, 2>() : fast == 1 ? tile64_configure<MT, false, 1>() : tile64_configure<MT, false, 0>();
-  if (e != hipSuccess) return e;
+  hipError_t e;
   const dim3 grid((cap_rows + 63) / 64, S, batch);
   if (fast == 2) head_tile64_kernel<MT, false, 2><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial);
   else if (fast == 1) head_tile64_kernel<MT, false, 1><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial);
@@ -656,8 +618,6 @@ static hipError_t run_tile64(const uint16_t* W, const uint16_t* H, const int32_t
                              float* logits, hipStream_t s) {
   constexpr int LDS = 4 * 16 * (1024 + kTilePad);
   const int fast = d % 512 != 0 ? 0 : (M == 64 ? 2 : 1);   // 2: every wavefront's sixteen hidden rows exist
-  hipError_t e = fast == 2 ? tile64_configure<MT, true, 2>() : fast == 1 ? tile64_configure<MT, true, 1>() : tile64_configure<MT, true, 0>();
-  if (e != hipSuccess) return e;
   const dim3 grid((cap_rows + 63) / 64, 1, batch);
   if (fast == 2) head_tile64_kernel<MT, true, 2><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
   else if (fast == 1) head_tile64_kernel<MT, true, 1><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
@@ -693,6 +653,49 @@ static hipError_t launch_head_64(const uint16_t* W, const uint16_t* H, const int
   }
   if (M <= 32) return run_tile64<2>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
   return run_tile64<4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+}
+
+// The dynamic-LDS limit of a kernel is a per-device attribute of the function.  Every instantiation that may ask
+// for more than the default 48 KB gets the chip's whole 160 KB once per device -- at nanospec_create or at the
+// first stateless call on the device, never in a launch path -- so that no later call can lower it under a live
+// state and no asynchronous call makes a runtime call that is not a launch.
+constexpr int kLdsLimit = 160 * 1024;
+
+template <int MT, int KS>
+static hipError_t configure_quad() {
+  const void* fns[] = {reinterpret_cast<const void*>(head_quad_kernel<1, 1, MT, KS, true>),
+                       reinterpret_cast<const void*>(head_quad_kernel<2, 1, MT, KS, true>),
+                       reinterpret_cast<const void*>(head_quad_kernel<4, 1, MT, KS, true>),
+                       reinterpret_cast<const void*>(head_quad_kernel<2, 2, MT, KS, true>)};
+  for (const void* f : fns) {
+    hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimit);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+template <int MT>
+static hipError_t configure_tile64() {
+  const void* fns[] = {reinterpret_cast<const void*>(head_tile64_kernel<MT, false, 0>), reinterpret_cast<const void*>(head_tile64_kernel<MT, false, 1>),
+                       reinterpret_cast<const void*>(head_tile64_kernel<MT, false, 2>), reinterpret_cast<const void*>(head_tile64_kernel<MT, true, 0>),
+                       reinterpret_cast<const void*>(head_tile64_kernel<MT, true, 1>), reinterpret_cast<const void*>(head_tile64_kernel<MT, true, 2>)};
+  for (const void* f : fns) {
+    hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimit);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+hipError_t head_configure_device() {
+  hipError_t e = configure_quad<1, 8>();
+  if (e == hipSuccess) e = configure_quad<2, 8>();
+  if (e == hipSuccess) e = configure_quad<3, 8>();
+  if (e == hipSuccess) e = configure_quad<3, 4>();
+  if (e == hipSuccess) e = configure_quad<4, 8>();
+  if (e == hipSuccess) e = configure_quad<4, 4>();
+  if (e == hipSuccess) e = configure_tile64<2>();
+  if (e == hipSuccess) e = configure_tile64<4>();
+  return e;
 }
 
 hipError_t launch_head(const void* W, const void* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,

@@ -742,20 +742,19 @@ hipError_t vocab_configure(nanospec_state* st) {
   if (st->unique_cap < st->m_cap * st->k_cap) return hipErrorInvalidValue;
   st->unique_lds_bytes = (3 * st->vp.nwords + 32 + kVocabThreads + st->unique_cap) * 4;
   st->fifo_lds_bytes = (3 * st->vp.nwords + 32 + kVocabThreads) * 4;
-  hipError_t e = hipSuccess;
-  if (st->vocab_lds_bytes > 48 * 1024)
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(vocab_apply_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            st->vocab_lds_bytes);
-  if (e == hipSuccess && st->unique_lds_bytes > 48 * 1024)
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(vocab_append_unique_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, st->unique_lds_bytes);
-  if (e == hipSuccess && st->unique_lds_bytes > 48 * 1024)
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(vocab_fifo_append_unique_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, st->unique_lds_bytes);
-  if (e == hipSuccess && st->fifo_lds_bytes > 48 * 1024)
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(vocab_fifo_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            st->fifo_lds_bytes);
-  return e;
+  return hipSuccess;
+}
+
+// Once per device: every vocabulary kernel may use the chip's whole LDS, whatever vocabulary size a state has
+// (a per-state limit would be lowered by the next, smaller state under a live larger one).
+hipError_t vocab_configure_device() {
+  const void* fns[] = {reinterpret_cast<const void*>(vocab_apply_kernel), reinterpret_cast<const void*>(vocab_append_unique_kernel),
+                       reinterpret_cast<const void*>(vocab_fifo_append_unique_kernel), reinterpret_cast<const void*>(vocab_fifo_kernel)};
+  for (const void* f : fns) {
+    hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 hipError_t launch_vocab_clear(const nanospec_state* st, hipStream_t s) {

@@ -55,6 +55,7 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly from Python instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-packed", action="store_true", help="skip the packed-buffer variant (the paper's own design)")
     ap.add_argument("--no-cold-check", action="store_true", help="skip timing the head over rotations of 16 / 32 / 48 weight copies")
     ap.add_argument("--traffic", default=None, help="HBM bytes per head launch from rocprofv3 --pmc runs (or omit)")
     args = ap.parse_args()
@@ -250,19 +251,85 @@ def main():
                     "stream_whole_matrix_GBps": round(full / f_us / 1e3, 1),
                     "head_over_gather": round(head_us / g_us, 3)}
 
-    # The paper's own system design (Sec. 3.3: rows of new active ids are copied into a pre-allocated packed
-    # buffer and the head is a dense product on that buffer) as a measured comparison point: the same active
-    # rows packed contiguously once (torch.index_select, outside the timed region), the dense kernel on the
-    # packed buffer with the same cold rotation, and the copy of one step's new rows into the buffer.
+    # The paper's own system design (Sec. 3.3 asynchronous gathering; Table 4's gather row; Table 5's Indexed GEMM
+    # against async gather) through the library's packed-buffer variant: a slot-stable packed copy of the active
+    # rows, nanospec_packed_gather copying only the rows of ids that entered, nanospec_packed_head as a dense
+    # product on the buffer.  Cold like the fused head: NP states with their own packed buffers are rotated (NP x
+    # ~30 MB of packed rows against the 256 MB Infinity Cache).  The dual-stream form: a stand-in backbone (a
+    # read of 1 GB, what a draft layer stack streams) on the main stream, update + gather on a second stream of
+    # equal priority, one event wait in front of the head -- against the same work on one stream.
     packed_variant = None
-    if Bn == 1 and M <= 16 and not args.no_dense:           # the stateless dense entry has no split-K workspace for wider trees
-        act0 = to_dev(st.read_active()[0].astype(np.int64))
-        n0 = int(act0.numel())
-        packed = [Wd[r].index_select(0, act0).contiguous() for r in range(R)]
-        pl = torch.empty((M, n0), dtype=torch.float32, device="cuda")
-        packed_us = train(lambda i, r, cs: B.nanospec_dense_head(packed[r % R], Hd[r % NH], n0, d, M, pl, cs), 240)
-        packed_variant = {"packed_dense_head_us": round(packed_us, 2), "fused_gather_head_us": round(head_us, 2), "rows": n0}
-        del packed
+    if Bn == 1 and d_T_steps is None and not args.no_packed:
+        NP = 12
+        pst = [B.State(V, d, 1, seqs["window"], seqs["topk_cap"], M, k) for _ in range(NP)]
+        for q in pst:
+            B.nanospec_packed_enable(q.h)
+
+        def reset_packed():
+            for q in pst:
+                B.nanospec_vocab_init(q.h, d_ctx, coff, d_T0, toff, stream)
+                B.nanospec_packed_gather(q.h, Wd[0], stream)
+        reset_packed()
+        packed_us = train(lambda i, r, cs: B.nanospec_packed_head(pst[r % NP].h, Hd[r % NH], M, logits, cs), 20 * NP)
+        # the per-step gather: update + gather against update alone, the steps' own appended ids, one state
+        q0 = pst[0]
+        nsteps = min(total_steps, 200)
+        init_q0 = lambda: (B.nanospec_vocab_init(q0.h, d_ctx, coff, d_T0, toff, stream), B.nanospec_packed_gather(q0.h, Wd[0], stream))
+
+        def upd_gather(i, r, cs):
+            B.nanospec_vocab_update(q0.h, d_new, offs[i], None, None, cs)
+            B.nanospec_packed_gather(q0.h, Wd[r % R], cs)
+        ug_us = timed(upd_gather, 0, nsteps, reset=init_q0)[0] * 1e3 / nsteps
+        u_us = timed(lambda i, r, cs: B.nanospec_vocab_update(q0.h, d_new, offs[i], None, None, cs), 0, nsteps, reset=init_q0)[0] * 1e3 / nsteps
+        init_q0()
+        copied = 0
+        for i in range(nsteps):                                # rows copied per step (read back, untimed)
+            upd_gather(i, i, stream)
+            copied += q0.read_packed()[3]
+        # dual-stream overlap, issued eagerly (two streams of equal priority, events between them)
+        side = torch.cuda.Stream()
+        main = torch.cuda.current_stream()
+        sink2 = torch.zeros(1024, dtype=torch.uint8, device="cuda")
+        back_bytes = min(1 << 30, V * d * 2) // 16 * 16        # never past the end of a weight copy
+
+        def draft_step(i, overlap):
+            if overlap:
+                side.wait_stream(main)
+                B.nanospec_vocab_update(q0.h, d_new, offs[i % nsteps], None, None, side.cuda_stream)
+                B.nanospec_packed_gather(q0.h, Wd[i % R], side.cuda_stream)
+                B.nanospec_calib_stream_read(Wd[(i + 7) % R], back_bytes, sink2, main.cuda_stream)      # the stand-in backbone
+                main.wait_stream(side)
+            else:
+                B.nanospec_calib_stream_read(Wd[(i + 7) % R], back_bytes, sink2, main.cuda_stream)
+                B.nanospec_vocab_update(q0.h, d_new, offs[i % nsteps], None, None, main.cuda_stream)
+                B.nanospec_packed_gather(q0.h, Wd[i % R], main.cuda_stream)
+            B.nanospec_packed_head(q0.h, Hd[i % NH], M, logits, main.cuda_stream)
+            B.nanospec_topk_remap(q0.h, logits, M, k, out_ids, out_vals, main.cuda_stream)
+
+        def eager(overlap, count=100):
+            ts = []
+            for rep in range(5):
+                init_q0()
+                for i in range(8):
+                    draft_step(i, overlap)
+                torch.cuda.synchronize()
+                e0.record(main)
+                for i in range(8, 8 + count):
+                    draft_step(i, overlap)
+                e1.record(main)
+                torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1) * 1e3 / count)
+            return float(np.median(ts))
+        back_us = train(lambda i, r, cs: B.nanospec_calib_stream_read(Wd[r % R], back_bytes, sink2, cs), 2 * ROT)
+        seq_us, ovl_us = eager(False), eager(True)
+        packed_variant = {"packed_head_us": round(packed_us, 2), "fused_gather_head_us": round(head_us, 2),
+                          "update_plus_gather_us": round(ug_us, 2), "update_alone_us": round(u_us, 2),
+                          "gather_us_per_step": round(ug_us - u_us, 2), "rows_copied_per_step": round(copied / nsteps, 2),
+                          "standin_backbone_us": round(back_us, 1),
+                          "draft_step_one_stream_us": round(seq_us, 1), "draft_step_gather_on_second_stream_us": round(ovl_us, 1),
+                          "note": "draft step = stand-in backbone + update + gather + packed head + top-k, issued eagerly"}
+        for q in pst:
+            q.close()
 
     # the one-off stream initialisation (S(0) = context, T = T0; clear + apply kernels), on a scratch state
     st_i = B.State(V, d, Bn, seqs["window"], seqs["topk_cap"], M, k)

@@ -174,6 +174,37 @@ NANOSPEC_API nanospec_status nanospec_vocab_view(const nanospec_state* st, const
 NANOSPEC_API nanospec_status nanospec_sparse_head(nanospec_state* st, const void* d_W_bf16, const void* d_H_bf16, int32_t M,
                                      float* d_logits, void* hip_stream);
 
+/* The paper's own system design as a variant of the head (Sec. 3.3 "Avoiding sparse computation via asynchronous
+ * gathering"; Alg. 1 Gather_Async; the weight-gather row of Table 4; the repacked-weights row of Table 6): a
+ * pre-allocated packed buffer of `capacity` rows holds a copy of every active row of W_head; after a vocabulary
+ * update only the rows of ids that entered the active set are copied in, and the head is a dense product on
+ * the packed buffer.  Slots are stable (an id keeps its slot while it stays active; an entering id takes the
+ * lowest free slot), and the logits still come out in the layout of nanospec_sparse_head (column j = j-th
+ * active id ascending), so nanospec_topk_remap / nanospec_topk_logprob_remap apply unchanged, ties by lower id
+ * included.  One sequence per state (batch == 1).
+ *   nanospec_packed_bytes  : device bytes nanospec_packed_enable allocates (capacity*d*2 for the rows -- 24 MiB at
+ *                            the paper's W_max = 3072, d = 4096 -- plus V*4 + 20*capacity bytes of slot tables).
+ *   nanospec_packed_enable : allocate and clear them.  Synchronous; idempotent.  Errors: EINVAL (batch != 1), ENOMEM, EHIP.
+ *   nanospec_packed_gather : bring the buffer in line with the current active list: free the slots of ids that
+ *                            left, give every id without a slot one, copy those rows W[id] -> buffer[slot], refresh
+ *                            the slot -> column map.  Two launches on `hip_stream`, which may be a second stream
+ *                            running beside the draft backbone; the caller orders it after the vocabulary call
+ *                            and before nanospec_packed_head with events (the paper's dual-stream pipeline).  The
+ *                            first call after nanospec_vocab_init, a T replacement or a long append copies many
+ *                            rows, a decoding step a handful.  Asynchronous.  Errors: EINVAL (not enabled), EHIP.
+ *   nanospec_packed_head   : logits as nanospec_sparse_head, computed from the packed buffer (W_head is not
+ *                            touched).  Asynchronous.  Errors: EINVAL, ECAPACITY (M > m_cap).
+ *   nanospec_packed_view   : borrowed device views for inspection: the row buffer bf16 [capacity][d], the id
+ *                            held by each slot (-1 free), each slot's logit column (-1 none), and two counters
+ *                            {slots that may hold a row, rows copied by the last gather}. */
+NANOSPEC_API int64_t nanospec_packed_bytes(const nanospec_state* st);
+NANOSPEC_API nanospec_status nanospec_packed_enable(nanospec_state* st);
+NANOSPEC_API nanospec_status nanospec_packed_gather(nanospec_state* st, const void* d_W_bf16, void* hip_stream);
+NANOSPEC_API nanospec_status nanospec_packed_head(nanospec_state* st, const void* d_H_bf16, int32_t M, float* d_logits,
+                                                  void* hip_stream);
+NANOSPEC_API nanospec_status nanospec_packed_view(const nanospec_state* st, const void** d_buf, const int32_t** d_slot_id,
+                                                  const int32_t** d_out_pos, const int32_t** d_counts);
+
 /* Draft-token selection, SelectDraftTokens(z', I) of Alg. 1 with the operator T_K of Sec. 3.2:
  * for every (b, m) the k largest of logits[b][m][0..n_b), ordered by value descending then global
  * id ascending (+0 and -0 tie), written as global ids and values.  Slots beyond n_b get id -1

@@ -25,6 +25,7 @@ EXPORTS = [
     "nanospec_set_stream_policy", "nanospec_vocab_init", "nanospec_vocab_update", "nanospec_vocab_append_unique", "nanospec_vocab_view", "nanospec_sparse_head",
     "nanospec_topk_remap", "nanospec_topk_logprob_remap", "nanospec_dense_head", "nanospec_dense_topk_workspace", "nanospec_dense_topk",
     "nanospec_dense_topk_static_limit", "nanospec_dense_topk_static",
+    "nanospec_packed_bytes", "nanospec_packed_enable", "nanospec_packed_gather", "nanospec_packed_head", "nanospec_packed_view",
     "nanospec_calib_stream_read", "nanospec_calib_gather_read", "nanospec_last_device_error",
 ]
 
@@ -76,9 +77,16 @@ def lib() -> C.CDLL:
         L.nanospec_dense_topk_static_limit.restype = i64
         L.nanospec_dense_topk_static_limit.argtypes = []
         L.nanospec_dense_topk_static.argtypes = [vp, i32, i32, i32, vp, vp, vp]
+        L.nanospec_packed_bytes.restype = i64
+        L.nanospec_packed_bytes.argtypes = [vp]
+        L.nanospec_packed_enable.argtypes = [vp]
+        L.nanospec_packed_gather.argtypes = [vp, vp, vp]
+        L.nanospec_packed_head.argtypes = [vp, vp, i32, vp, vp]
+        L.nanospec_packed_view.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp)]
         L.nanospec_last_device_error.argtypes = [vp, i32p, vp]
         for name in EXPORTS:
-            if name not in ("nanospec_status_string", "nanospec_dense_topk_workspace", "nanospec_dense_topk_static_limit"):
+            if name not in ("nanospec_status_string", "nanospec_dense_topk_workspace", "nanospec_dense_topk_static_limit",
+                            "nanospec_packed_bytes"):
                 getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -177,6 +185,8 @@ def nanospec_topk_logprob_remap(st, d_logits, M, k, d_out_ids, d_out_logprob, st
 
 
 def nanospec_calib_stream_read(d_buf, nbytes, d_sink, stream=None):
+    if not isinstance(d_buf, int) and nbytes > d_buf.numel() * d_buf.element_size():      # the library cannot know the buffer's size
+        raise ValueError(f"nanospec_calib_stream_read: {nbytes} bytes asked of a buffer of {d_buf.numel() * d_buf.element_size()}")
     _check(lib().nanospec_calib_stream_read(_ptr(d_buf), nbytes, _ptr(d_sink), _stream(stream)), "nanospec_calib_stream_read")
 
 
@@ -207,6 +217,29 @@ def nanospec_dense_topk_static(d_logits, V, M_total, k, d_out_ids, d_out_vals, s
                                             _stream(stream)), "nanospec_dense_topk_static")
 
 
+def nanospec_packed_bytes(st) -> int:
+    return int(lib().nanospec_packed_bytes(st))
+
+
+def nanospec_packed_enable(st):
+    _check(lib().nanospec_packed_enable(st), "nanospec_packed_enable")
+
+
+def nanospec_packed_gather(st, d_W, stream=None):
+    _check(lib().nanospec_packed_gather(st, _ptr(d_W), _stream(stream)), "nanospec_packed_gather")
+
+
+def nanospec_packed_head(st, d_H, M, d_logits, stream=None):
+    _check(lib().nanospec_packed_head(st, _ptr(d_H), M, _ptr(d_logits), _stream(stream)), "nanospec_packed_head")
+
+
+def nanospec_packed_view(st):
+    """(buf_ptr, slot_id_ptr, out_pos_ptr, counts_ptr): raw device addresses borrowed from the state."""
+    a, b, c, d = C.c_void_p(), C.c_void_p(), C.c_void_p(), C.c_void_p()
+    _check(lib().nanospec_packed_view(st, C.byref(a), C.byref(b), C.byref(c), C.byref(d)), "nanospec_packed_view")
+    return a.value, b.value, c.value, d.value
+
+
 def nanospec_last_device_error(st, stream=None) -> int:
     f = C.c_int32()
     _check(lib().nanospec_last_device_error(st, C.byref(f), _stream(stream)), "nanospec_last_device_error")
@@ -231,6 +264,16 @@ class State:
             self.close()
         except Exception:
             pass
+
+    def read_packed(self):
+        """host copies of the packed-buffer tables: (slot ids int32[capacity], logit columns int32[capacity],
+        slots that may hold a row, rows copied by the last gather, row buffer as uint16 [capacity][d])."""
+        import torch
+        torch.cuda.synchronize()
+        buf, sid, pos, cnt = nanospec_packed_view(self.h)
+        c = _copy_from_device(cnt, 2, np.int32)
+        return (_copy_from_device(sid, self.capacity, np.int32), _copy_from_device(pos, self.capacity, np.int32), int(c[0]), int(c[1]),
+                _copy_from_device(buf, self.capacity * self.d, np.uint16).reshape(self.capacity, self.d))
 
     def read_active(self):
         """copy the active id lists back to the host: list of int32 arrays (one per sequence)."""

@@ -183,10 +183,73 @@ nanospec_status nanospec_create(nanospec_state** out, int32_t V, int32_t d, int3
 
 nanospec_status nanospec_destroy(nanospec_state* st) {
   if (!st) return NANOSPEC_EINVAL;
+  if (st->pk_base) (void)hipFree(st->pk_base);
   hipError_t e1 = hipFree(st->base);
   hipError_t e2 = hipHostFree(st->h_err_pinned);
   delete st;
   return (e1 == hipSuccess && e2 == hipSuccess) ? NANOSPEC_OK : NANOSPEC_EHIP;
+}
+
+int64_t nanospec_packed_bytes(const nanospec_state* st) {
+  if (!st) return -1;
+  const int64_t cap = st->vp.cap;
+  return round_up(cap * st->d * 2, 256) + round_up((int64_t)st->V * 4, 256) + 5 * round_up(cap * 4, 256) + 256;
+}
+
+nanospec_status nanospec_packed_enable(nanospec_state* st) {
+  if (!st || wrong_device(st) || st->batch != 1) return NANOSPEC_EINVAL;
+  if (st->pk_base) return NANOSPEC_OK;
+  const int64_t cap = st->vp.cap;
+  char* base = nullptr;
+  if (hipMalloc(reinterpret_cast<void**>(&base), nanospec_packed_bytes(st)) != hipSuccess) {
+    (void)hipGetLastError();
+    return NANOSPEC_ENOMEM;
+  }
+  char* p = base;
+  auto take = [&](int64_t bytes) { char* r = p; p += round_up(bytes, 256); return r; };
+  PackedPtrs& k = st->pk;
+  k.cap = (int32_t)cap;
+  k.buf = reinterpret_cast<uint16_t*>(take(cap * st->d * 2));
+  k.slot_of = reinterpret_cast<int32_t*>(take((int64_t)st->V * 4));
+  k.slot_id = reinterpret_cast<int32_t*>(take(cap * 4));
+  k.out_pos = reinterpret_cast<int32_t*>(take(cap * 4));
+  k.free_list = reinterpret_cast<int32_t*>(take(cap * 4));
+  k.copy_list = reinterpret_cast<int32_t*>(take(2 * cap * 4));
+  k.scal = reinterpret_cast<int32_t*>(take(8));
+  st->pk_base = base;
+  if (launch_packed_reset(st, nullptr) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipFree(base);
+    st->pk_base = nullptr;
+    k.buf = nullptr;
+    return NANOSPEC_EHIP;
+  }
+  return NANOSPEC_OK;
+}
+
+nanospec_status nanospec_packed_gather(nanospec_state* st, const void* d_W_bf16, void* hip_stream) {
+  if (!st || !d_W_bf16 || wrong_device(st) || !st->pk_base) return NANOSPEC_EINVAL;
+  return launch_packed_gather(st, d_W_bf16, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;
+}
+
+nanospec_status nanospec_packed_head(nanospec_state* st, const void* d_H_bf16, int32_t M, float* d_logits, void* hip_stream) {
+  if (!st || !d_H_bf16 || !d_logits || M < 1 || wrong_device(st) || !st->pk_base) return NANOSPEC_EINVAL;
+  if (M > st->m_cap) return NANOSPEC_ECAPACITY;
+  const int32_t cap = st->vp.cap;
+  // a dense product over the slots that may hold a row (count on the device), logits to the columns of the ascending list
+  hipError_t e = launch_head(st->pk.buf, d_H_bf16, nullptr, st->pk.scal, 0, cap, cap, 1, M, st->d, cap, cap, d_logits, st->partial,
+                             st->partial_bytes, st->pk.out_pos, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;
+}
+
+nanospec_status nanospec_packed_view(const nanospec_state* st, const void** d_buf, const int32_t** d_slot_id, const int32_t** d_out_pos,
+                                     const int32_t** d_counts) {
+  if (!st || !st->pk_base) return NANOSPEC_EINVAL;
+  if (d_buf) *d_buf = st->pk.buf;
+  if (d_slot_id) *d_slot_id = st->pk.slot_id;
+  if (d_out_pos) *d_out_pos = st->pk.out_pos;
+  if (d_counts) *d_counts = st->pk.scal;
+  return NANOSPEC_OK;
 }
 
 nanospec_status nanospec_set_stream_policy(nanospec_state* st, int32_t policy) {
@@ -228,7 +291,7 @@ nanospec_status nanospec_sparse_head(nanospec_state* st, const void* d_W_bf16, c
   if (!st || !d_W_bf16 || !d_H_bf16 || !d_logits || M < 1 || wrong_device(st)) return NANOSPEC_EINVAL;
   if (M > st->m_cap) return NANOSPEC_ECAPACITY;
   hipError_t e = launch_head(d_W_bf16, d_H_bf16, st->vp.ids, st->vp.n, 0, st->vp.cap, st->V, st->batch, M, st->d, st->vp.cap,
-                             st->vp.cap, d_logits, st->partial, st->partial_bytes, static_cast<hipStream_t>(hip_stream));
+                             st->vp.cap, d_logits, st->partial, st->partial_bytes, nullptr, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;
 }
 
@@ -256,7 +319,7 @@ nanospec_status nanospec_dense_head(const void* d_W_bf16, const void* d_H_bf16, 
                                     float* d_logits, void* hip_stream) {
   if (!d_W_bf16 || !d_H_bf16 || !d_logits || V < 1 || d < 8 || d % 8 != 0 || M_total < 1) return NANOSPEC_EINVAL;
   if (ensure_device_configured() != hipSuccess) return NANOSPEC_EHIP;   // a flag test after the first call on the device
-  hipError_t e = launch_head(d_W_bf16, d_H_bf16, nullptr, nullptr, V, V, V, 1, M_total, d, V, 0, d_logits, nullptr, 0,
+  hipError_t e = launch_head(d_W_bf16, d_H_bf16, nullptr, nullptr, V, V, V, 1, M_total, d, V, 0, d_logits, nullptr, 0, nullptr,
                              static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;
 }

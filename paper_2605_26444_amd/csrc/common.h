@@ -31,6 +31,18 @@ struct VocabPtrs {
   int32_t V, window, nwords, cap;
 };
 
+// Packed-buffer variant (one sequence): slot tables and the row copies.
+struct PackedPtrs {
+  uint16_t* buf;        // [cap][d] bf16: one row per slot
+  int32_t* slot_of;     // [V]   slot that holds the id's row, or -1
+  int32_t* slot_id;     // [cap] id whose row the slot holds, or -1
+  int32_t* out_pos;     // [cap] position of that id in the ascending active list, or -1
+  int32_t* free_list;   // [cap] scratch of one gather: free slots ascending
+  int32_t* copy_list;   // [cap][2] scratch of one gather: (id, slot) of the rows to copy
+  int32_t* scal;        // [0] slots that may hold a row (highest slot in use + 1), [1] rows on the copy list
+  int32_t cap;
+};
+
 }  // namespace nanospec
 
 struct nanospec_state {
@@ -45,6 +57,8 @@ struct nanospec_state {
   int32_t* h_err_pinned;    // pinned host word for reading the device flags
   int vocab_lds_bytes, unique_lds_bytes, unique_cap, fifo_lds_bytes;
   int32_t policy, policy_next;   // vocabulary reading in force / chosen for the next init
+  nanospec::PackedPtrs pk;       // packed-buffer variant; pk.buf == nullptr until nanospec_packed_enable
+  char* pk_base;                 // its one device allocation
 };
 
 namespace nanospec {
@@ -61,15 +75,21 @@ hipError_t launch_vocab_append_unique(const nanospec_state* st, const int32_t* d
 // head.hip
 hipError_t head_configure_device();
 // logits[b][m][j] for j < n_b (n read on the device).  ids == nullptr: identity list of n_fixed rows.
+// opos != nullptr (row stride ids_stride): row j's logits go to column opos[j] instead, nowhere if negative.
 hipError_t launch_head(const void* W, const void* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
                        int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld_logits,
-                       int64_t ids_stride, float* logits, float* partial, int64_t partial_bytes, hipStream_t s);
+                       int64_t ids_stride, float* logits, float* partial, int64_t partial_bytes, const int32_t* opos,
+                       hipStream_t s);
 
 // topk.hip
 int64_t topk_workspace_bytes(int32_t cap, int32_t rows, int32_t k);
 hipError_t launch_topk(const float* logits, int64_t ld, const int32_t* ids, int64_t ids_stride, const int32_t* n_dev,
                        int32_t n_fixed, int32_t cap, int32_t batch, int32_t M, int32_t k, int32_t* out_ids,
                        float* out_vals, bool logprob, char* ws, int64_t ws_bytes, hipStream_t s);
+
+// packed.hip
+hipError_t launch_packed_reset(const nanospec_state* st, hipStream_t s);
+hipError_t launch_packed_gather(const nanospec_state* st, const void* W, hipStream_t s);
 
 // calib.hip
 hipError_t launch_calib_stream(const void* buf, int64_t bytes, void* sink, hipStream_t s);

@@ -34,13 +34,15 @@ template <int MT>
 __global__ __launch_bounds__(256) void head_generic_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
                                                            const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
                                                            int n_fixed, int M, int d, int64_t ld, int64_t ids_stride,
-                                                           float* __restrict__ logits) {
+                                                           float* __restrict__ logits, const int32_t* __restrict__ opos) {
   const int b = blockIdx.z;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = n_dev ? n_dev[b] : n_fixed;
   const int j = blockIdx.x * 4 + wave;
   if (j >= n) return;
   const int64_t row = ids ? ids[b * ids_stride + j] : j;
+  const int jo = opos ? opos[b * ids_stride + j] : j;     // where this row's logits go (a row nobody asks for: nowhere)
+  if (jo < 0) return;
   const uint16_t* w = W + row * d;
   for (int m0 = 0; m0 < M; m0 += MT) {
     float acc[MT];
@@ -59,7 +61,7 @@ __global__ __launch_bounds__(256) void head_generic_kernel(const uint16_t* __res
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
       const float s = wave_sum(acc[t]);
-      if (lane == 0 && m0 + t < M) logits[((int64_t)b * M + m0 + t) * ld + j] = s;
+      if (lane == 0 && m0 + t < M) logits[((int64_t)b * M + m0 + t) * ld + jo] = s;
     }
   }
 }
@@ -92,7 +94,8 @@ template <int RT, int MT, int KS, int NW, bool FAST>
 __global__ __launch_bounds__(64 * NW) void head_quad_private_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
                                                         const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
                                                         int n_fixed, int V, int M, int d, int64_t ld, int64_t ids_stride,
-                                                        float* __restrict__ logits, int seq_first) {
+                                                        float* __restrict__ logits, int seq_first,
+                                                        const int32_t* __restrict__ opos) {
   constexpr int ROWS = 4 * RT;
   __shared__ float red[NW][RT * MT * 16];
   // Several sequences: the grid is (sequence, tile) with the sequence fastest, so the workgroups in
@@ -144,6 +147,11 @@ __global__ __launch_bounds__(64 * NW) void head_quad_private_kernel(const uint16
     for (int r = 0; r < ROWS; ++r) idr[r] = j0 + r;
   }
   const int n = n_dev ? n_dev[b] : n_fixed;
+  // where the logit this thread will store goes: column j, or -- for rows kept in an order of their own -- the
+  // column listed for row j (negative: nowhere); asked for now, used after the K loop
+  static_assert(RT * MT * 16 <= 64 * NW, "one output per thread");
+  int jout = j0 + (threadIdx.x / (MT * 16)) * 4 + (threadIdx.x % 16) / 4;
+  if (opos) jout = threadIdx.x < RT * MT * 16 && jout < (int)ids_stride ? opos[b * ids_stride + jout] : -1;
   // hidden rows of the first K-iteration depend on the arguments only: they stream in from L2
   // while the ids are still on their way
   u32x4 hv[MT][KS];
@@ -204,27 +212,27 @@ __global__ __launch_bounds__(64 * NW) void head_quad_private_kernel(const uint16
   for (int o = threadIdx.x; o < RT * MT * 16; o += 64 * NW) {
     const int rt = o / (MT * 16), mt = (o / 16) % MT, r = (o % 16) / 4, mm = o % 4;
     const int j = j0 + rt * 4 + r, m = mt * 4 + mm;
-    if (j >= n || m >= M) continue;
+    if (j >= n || m >= M || jout < 0) continue;
     float s = red[0][o];
 #pragma unroll
     for (int ww = 1; ww < NW; ++ww) s += red[ww][o];
-    logits[((int64_t)b * M + m) * ld + j] = s;
+    logits[((int64_t)b * M + m) * ld + jout] = s;
   }
 }
 
 template <int RT, int MT, int KS, int NW>
 static hipError_t run_quad_private(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
                            int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride,
-                           float* logits, hipStream_t s) {
+                           float* logits, const int32_t* opos, hipStream_t s) {
   const int tiles = (cap_rows + 4 * RT - 1) / (4 * RT);
   const int seq_first = batch > 1 && tiles <= 65535;
   const dim3 grid = seq_first ? dim3(batch, tiles, 1) : dim3(tiles, 1, batch);
   if (d % (NW * 128 * KS) == 0)
     head_quad_private_kernel<RT, MT, KS, NW, true><<<grid, 64 * NW, 0, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride,
-                                                                            logits, seq_first);
+                                                                            logits, seq_first, opos);
   else
     head_quad_private_kernel<RT, MT, KS, NW, false><<<grid, 64 * NW, 0, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride,
-                                                                             logits, seq_first);
+                                                                             logits, seq_first, opos);
   return hipGetLastError();
 }
 
@@ -251,7 +259,8 @@ template <int NRG, int RT, int MT, int KS, bool ONEK>
 __global__ __launch_bounds__(256 * NRG) void head_quad_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
                                                               const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
                                                               int n_fixed, int V, int M, int d, int64_t ld, int64_t ids_stride,
-                                                              float* __restrict__ logits, int seq_first) {
+                                                              float* __restrict__ logits, int seq_first,
+                                                              const int32_t* __restrict__ opos) {
   constexpr int HI = MT * KS;                      // load instructions per hidden-row K-quarter slice
   constexpr int HPW = (HI + NRG - 1) / NRG;        // of which each sharing wavefront fetches this many
   constexpr int RPG = 4 * RT;                      // rows per row group
@@ -301,6 +310,15 @@ __global__ __launch_bounds__(256 * NRG) void head_quad_kernel(const uint16_t* __
   int vzero = 0;
   if (UNCOND) asm volatile("" : "+v"(vzero));             // a zero the compiler cannot see through: keeps the load below on the vector path
   const int n = n_dev ? n_dev[b + vzero] : n_fixed;
+  // where the logit this thread will store goes (see head_quad_private_kernel); asked for now, used at the end
+  static_assert(NOUT <= 256, "one output per thread");
+  int jout = -1;
+  {
+    const int g = threadIdx.x / NOUT, oo = threadIdx.x % NOUT;
+    const int j = (tile * NRG + g) * RPG + (oo / (MT * 16)) * 4 + (oo % 16) / 4;
+    jout = j;
+    if (opos) jout = threadIdx.x < NRG * NOUT && j < (int)ids_stride ? opos[b * ids_stride + j] : -1;
+  }
 
   bool hok[HPW];
   auto load_h = [&](int kb, u32x4(&hv)[HPW]) {
@@ -386,24 +404,25 @@ __global__ __launch_bounds__(256 * NRG) void head_quad_kernel(const uint16_t* __
     const int g = o / NOUT, oo = o % NOUT;
     const int rt = oo / (MT * 16), mt = (oo / 16) % MT, r = (oo % 16) / 4, mm = oo % 4;
     const int j = (tile * NRG + g) * RPG + rt * 4 + r, m = mt * 4 + mm;
-    if (j >= n || m >= M) continue;
+    if (j >= n || m >= M || jout < 0) continue;
     const float* rr = red + (g * 4) * NOUT + oo;
     const float s = ((rr[0] + rr[NOUT]) + rr[2 * NOUT]) + rr[3 * NOUT];
-    logits[((int64_t)b * M + m) * ld + j] = s;
+    logits[((int64_t)b * M + m) * ld + jout] = s;
   }
 }
 
 template <int NRG, int RT, int MT, int KS>
 static hipError_t run_quad(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
                            int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride,
-                           float* logits, hipStream_t s) {
+                           float* logits, const int32_t* opos, hipStream_t s) {
   constexpr int ROWS = 4 * RT * NRG;
   constexpr int LDS = 4 * MT * KS * 1024 + 4 * NRG * (RT * MT * 16) * 4;
   const int tiles = (cap_rows + ROWS - 1) / ROWS;
   const int seq_first = batch > 1 && tiles <= 65535;
   const dim3 grid = seq_first ? dim3(batch, tiles, 1) : dim3(tiles, 1, batch);
   if (d > 512 * KS) return hipErrorInvalidValue;          // callers send longer rows to the K-loop kernel
-  head_quad_kernel<NRG, RT, MT, KS, true><<<grid, 256 * NRG, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits, seq_first);
+  head_quad_kernel<NRG, RT, MT, KS, true><<<grid, 256 * NRG, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits, seq_first,
+                                                                       opos);
   return hipGetLastError();
 }
 
@@ -418,17 +437,17 @@ static hipError_t run_quad(const uint16_t* W, const uint16_t* H, const int32_t* 
 template <int MT, int KS>
 static hipError_t run_quad_auto(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
                                 int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld,
-                                int64_t ids_stride, float* logits, hipStream_t s) {
+                                int64_t ids_stride, float* logits, const int32_t* opos, hipStream_t s) {
   const int64_t rows = (int64_t)cap_rows * batch;
   if (d > 512 * KS) {
-    if (rows < 8 * 180) return run_quad_private<1, MT, KS, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
-    if (MT <= 2 || rows < 8192) return run_quad_private<2, MT, KS, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
-    return run_quad_private<4, MT, KS, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+    if (rows < 8 * 180) return run_quad_private<1, MT, KS, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
+    if (MT <= 2 || rows < 8192) return run_quad_private<2, MT, KS, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
+    return run_quad_private<4, MT, KS, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
   }
-  if (batch > 1 && rows >= 8192) return run_quad<2, 2, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
-  if (rows >= 16 * 180) return run_quad<4, 1, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
-  if (rows >= 8 * 180) return run_quad<2, 1, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
-  return run_quad<1, 1, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+  if (batch > 1 && rows >= 8192) return run_quad<2, 2, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
+  if (rows >= 16 * 180) return run_quad<4, 1, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
+  if (rows >= 8 * 180) return run_quad<2, 1, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
+  return run_quad<1, 1, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
 }
 
 // Matrix-core kernel for wide draft trees (16 < M <= 64).  A workgroup owns 64 rows (one 16-row
@@ -458,7 +477,7 @@ template <int MT, bool LOOPK, int FAST>
 __global__ __launch_bounds__(256) void head_tile64_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
                                                           const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
                                                           int n_fixed, int V, int M, int d, int64_t ld, int64_t ids_stride,
-                                                          float* __restrict__ out) {
+                                                          float* __restrict__ out, const int32_t* __restrict__ opos) {
   constexpr int STRB = 1024 + kTilePad;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int b = blockIdx.z, batch = gridDim.z;
@@ -475,6 +494,12 @@ __global__ __launch_bounds__(256) void head_tile64_kernel(const uint16_t* __rest
   int vzero = 0;
   if (FAST) asm volatile("" : "+v"(vzero));               // keeps the row count's load on the vector path, in order behind the ids
   const int nv = n_dev ? n_dev[b + vzero] : n_fixed;
+  // rows kept in an order of their own (LOOPK only): the columns their logits go to, four per lane, asked for now
+  int4 jo4 = make_int4(0, 0, 0, 0);
+  if (LOOPK && opos) {
+    const int jq = j0 + 4 * (lane >> 4);
+    jo4 = jq + 3 < (int)ids_stride ? *reinterpret_cast<const int4*>(opos + b * ids_stride + jq) : make_int4(-1, -1, -1, -1);
+  }
   u32x4 hv[16], wv[16];
   int n = nv;
   auto load_slice = [&](int sl) {
@@ -564,7 +589,13 @@ __global__ __launch_bounds__(256) void head_tile64_kernel(const uint16_t* __rest
     if (m >= M || j >= n) continue;
     float* dst = LOOPK ? out + ((int64_t)b * M + m) * ld + j
                        : out + (((int64_t)blockIdx.y * batch + b) * M + m) * ld + j;   // ld = plane row stride
-    if ((ld & 3) == 0 && (LOOPK ? j + 3 < n : true)) {
+    if (LOOPK && opos) {
+      float* rowp = out + ((int64_t)b * M + m) * ld;
+      const int jo[4] = {jo4.x, jo4.y, jo4.z, jo4.w};
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        if (j + v < n && jo[v] >= 0) rowp[jo[v]] = acc[mt][v];
+    } else if ((ld & 3) == 0 && (LOOPK ? j + 3 < n : true)) {
       *reinterpret_cast<f32x4*>(dst) = acc[mt];
     } else {
 #pragma unroll
@@ -575,10 +606,13 @@ __global__ __launch_bounds__(256) void head_tile64_kernel(const uint16_t* __rest
 }
 
 __global__ __launch_bounds__(256) void head_splitk_reduce_kernel(const float* __restrict__ partial, const int32_t* __restrict__ n_dev,
-                                                                 int S, int M, int cap, int64_t ld, float* __restrict__ logits) {
+                                                                 int S, int M, int cap, int64_t ld, float* __restrict__ logits,
+                                                                 const int32_t* __restrict__ opos) {
   const int b = blockIdx.z, m = blockIdx.y, batch = gridDim.z;
   const int j = (blockIdx.x * 256 + threadIdx.x) * 4;
   if (j >= n_dev[b]) return;
+  int4 jo4 = make_int4(0, 0, 0, 0);
+  if (opos) jo4 = *reinterpret_cast<const int4*>(opos + (int64_t)b * cap + j);   // j + 3 < cap: cap is a multiple of 64
   const int64_t plane = (int64_t)batch * M * cap;
   const float* p = partial + ((int64_t)b * M + m) * cap + j;
   // eight planes are fetched before the first add so that their latencies overlap; the adds keep slice order
@@ -591,37 +625,46 @@ __global__ __launch_bounds__(256) void head_splitk_reduce_kernel(const float* __
 #pragma unroll
     for (int i = 0; i < 8; ++i) s += v[i];
   }
+  if (opos) {
+    float* rowp = logits + ((int64_t)b * M + m) * ld;
+    const int jo[4] = {jo4.x, jo4.y, jo4.z, jo4.w};
+    const int n = n_dev[b];
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+      if (j + v < n && jo[v] >= 0) rowp[jo[v]] = s[v];
+    return;
+  }
   *reinterpret_cast<f32x4*>(logits + ((int64_t)b * M + m) * ld + j) = s;
 }
 
 template <int MT>
 static hipError_t run_splitk(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t cap_rows,
                              int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride, float* logits,
-                             float* partial, int S, hipStream_t s) {
+                             float* partial, int S, const int32_t* opos, hipStream_t s) {
   constexpr int LDS = 4 * 16 * (1024 + kTilePad);
   const int fast = d % 512 != 0 ? 0 : (M == 64 ? 2 : 1);   // 2: every wavefront's sixteen hidden rows exist
   hipError_t e;
   const dim3 grid((cap_rows + 63) / 64, S, batch);
-  if (fast == 2) head_tile64_kernel<MT, false, 2><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial);
-  else if (fast == 1) head_tile64_kernel<MT, false, 1><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial);
-  else head_tile64_kernel<MT, false, 0><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial);
+  if (fast == 2) head_tile64_kernel<MT, false, 2><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial, nullptr);
+  else if (fast == 1) head_tile64_kernel<MT, false, 1><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial, nullptr);
+  else head_tile64_kernel<MT, false, 0><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial, nullptr);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   head_splitk_reduce_kernel<<<dim3((cap_rows / 4 + 255) / 256, M, batch), 256, 0, s>>>(partial, n_dev, S, M, cap_rows, ld,
-                                                                                    logits);
+                                                                                    logits, opos);
   return hipGetLastError();
 }
 
 template <int MT>
 static hipError_t run_tile64(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
                              int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld, int64_t ids_stride,
-                             float* logits, hipStream_t s) {
+                             float* logits, const int32_t* opos, hipStream_t s) {
   constexpr int LDS = 4 * 16 * (1024 + kTilePad);
   const int fast = d % 512 != 0 ? 0 : (M == 64 ? 2 : 1);   // 2: every wavefront's sixteen hidden rows exist
   const dim3 grid((cap_rows + 63) / 64, 1, batch);
-  if (fast == 2) head_tile64_kernel<MT, true, 2><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
-  else if (fast == 1) head_tile64_kernel<MT, true, 1><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
-  else head_tile64_kernel<MT, true, 0><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits);
+  if (fast == 2) head_tile64_kernel<MT, true, 2><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits, opos);
+  else if (fast == 1) head_tile64_kernel<MT, true, 1><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits, opos);
+  else head_tile64_kernel<MT, true, 0><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits, opos);
   return hipGetLastError();
 }
 
@@ -629,30 +672,30 @@ static hipError_t run_tile64(const uint16_t* W, const uint16_t* H, const int32_t
 static hipError_t launch_head_64(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev,
                                  int32_t n_fixed, int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d,
                                  int64_t ld, int64_t ids_stride, float* logits, float* partial, int64_t partial_bytes,
-                                 hipStream_t s) {
-  if (M <= 4) return run_quad_auto<1, 8>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
-  if (M <= 8) return run_quad_auto<2, 8>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+                                 const int32_t* opos, hipStream_t s) {
+  if (M <= 4) return run_quad_auto<1, 8>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
+  if (M <= 8) return run_quad_auto<2, 8>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
   // 9..16 hidden rows: 8 loads per row and wavefront when that makes d a single K-iteration (up to 128 KB of
   // LDS for the hidden-row operands), else 4
   if (M <= 12) {
-    if (d > 2048 && d <= 4096) return run_quad_auto<3, 8>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
-    return run_quad_auto<3, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+    if (d > 2048 && d <= 4096) return run_quad_auto<3, 8>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
+    return run_quad_auto<3, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
   }
   if (M <= 16) {
-    if (d > 2048 && d <= 4096) return run_quad_auto<4, 8>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
-    return run_quad_auto<4, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+    if (d > 2048 && d <= 4096) return run_quad_auto<4, 8>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
+    return run_quad_auto<4, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
   }
   // wide trees: split K across workgroups while the rows alone cannot fill the chip
   const int S = (d + 511) / 512;
   const int64_t need = (int64_t)S * batch * M * cap_rows * 4;
-  const bool split = ids != nullptr && n_dev != nullptr && partial != nullptr && S >= 2 && need <= partial_bytes &&
+  const bool split = n_dev != nullptr && partial != nullptr && S >= 2 && need <= partial_bytes &&
                      (int64_t)cap_rows * batch <= 16384 && cap_rows % 64 == 0 && ld % 4 == 0;
   if (split) {
-    if (M <= 32) return run_splitk<2>(W, H, ids, n_dev, cap_rows, V, batch, M, d, ld, ids_stride, logits, partial, S, s);
-    return run_splitk<4>(W, H, ids, n_dev, cap_rows, V, batch, M, d, ld, ids_stride, logits, partial, S, s);
+    if (M <= 32) return run_splitk<2>(W, H, ids, n_dev, cap_rows, V, batch, M, d, ld, ids_stride, logits, partial, S, opos, s);
+    return run_splitk<4>(W, H, ids, n_dev, cap_rows, V, batch, M, d, ld, ids_stride, logits, partial, S, opos, s);
   }
-  if (M <= 32) return run_tile64<2>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
-  return run_tile64<4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, s);
+  if (M <= 32) return run_tile64<2>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
+  return run_tile64<4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
 }
 
 // The dynamic-LDS limit of a kernel is a per-device attribute of the function.  Every instantiation that may ask
@@ -700,23 +743,23 @@ hipError_t head_configure_device() {
 
 hipError_t launch_head(const void* W, const void* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed,
                        int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld_logits, int64_t ids_stride,
-                       float* logits, float* partial, int64_t partial_bytes, hipStream_t s) {
+                       float* logits, float* partial, int64_t partial_bytes, const int32_t* opos, hipStream_t s) {
   const uint16_t* Wp = static_cast<const uint16_t*>(W);
   const uint16_t* Hp = static_cast<const uint16_t*>(H);
   if (M <= 64)
     return launch_head_64(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, partial,
-                          partial_bytes, s);
+                          partial_bytes, opos, s);
   if (batch == 1) {                       // many hidden rows of one sequence: 64 at a time
     for (int m0 = 0; m0 < M; m0 += 64) {
       const int mm = M - m0 < 64 ? M - m0 : 64;
       hipError_t e = launch_head_64(Wp, Hp + (int64_t)m0 * d, ids, n_dev, n_fixed, cap_rows, V, 1, mm, d, ld_logits, ids_stride,
-                                    logits + (int64_t)m0 * ld_logits, partial, partial_bytes, s);
+                                    logits + (int64_t)m0 * ld_logits, partial, partial_bytes, opos, s);
       if (e != hipSuccess) return e;
     }
     return hipSuccess;
   }
   dim3 grid((cap_rows + 3) / 4, 1, batch);
-  head_generic_kernel<8><<<grid, 256, 0, s>>>(Wp, Hp, ids, n_dev, n_fixed, M, d, ld_logits, ids_stride, logits);
+  head_generic_kernel<8><<<grid, 256, 0, s>>>(Wp, Hp, ids, n_dev, n_fixed, M, d, ld_logits, ids_stride, logits, opos);
   return hipGetLastError();
 }
 

@@ -158,6 +158,44 @@ def test_dense_entries_row_stride_not_a_multiple_of_four(d, M_total):
     _dense_entries_against_oracle(W, V, d, M_total, 10, 9200 + d + M_total, full=d <= 1032, n_sample=3000)
 
 
+@pytest.mark.parametrize("V,W,nT,alphabet", [(3000, 150, 60, 400), (128256, 1024, 2000, 5000), (50000, 300, 0, 350), (700, 64, 700, 700),
+                                            (200000, 6000, 100, 9000)])
+def test_feedback_of_active_ids(V, W, nT, alphabet):
+    """nanospec_vocab_append_unique with candidates drawn from the active set itself (what a closed draft loop
+    feeds back), 1 to 128 per call (the sets small enough to be sorted without the scratch bitmap): windows small
+    enough that every call evicts, rings full of repeats, ids held by T only, repeats and -1 padding among the
+    candidates, an id that leaves and is appended in the same call; every few calls a candidate that is not
+    active, and a plain update in between."""
+    rng = np.random.default_rng(V + W)
+    st = B.State(V, 64, 1, W, max(nT, 1), 8, 16)
+    orc = oracle.Vocab(V, W)
+    pool = rng.choice(V, alphabet, replace=False).astype(np.int32)
+    ctx = rng.choice(pool, 3 * W).astype(np.int32)
+    T = rng.choice(V, nT, replace=False).astype(np.int32)
+    B.nanospec_vocab_init(st.h, dev(ctx), [0, len(ctx)], dev_ids(T), [0, len(T)])
+    orc.init(ctx, T)
+    for step in range(40):
+        act = orc.active()
+        assert np.array_equal(st.read_active()[0], act), step
+        per = int(rng.choice([1, 7, 80, 128]))
+        cand = rng.choice(act, per).astype(np.int32)                       # members, with repeats
+        cand[rng.random(per) < 0.1] = -1                                   # padding
+        if step % 3 == 1:                                                  # ids about to leave the window, appended again
+            tail = ctx[-W:] if step == 1 else cand
+            cand[: min(per, 5)] = tail[: min(per, 5)]
+        if step % 7 == 6:
+            cand[0] = int(rng.integers(0, V))                              # most likely not active: everything is rebuilt
+        B.nanospec_vocab_append_unique(st.h, dev(cand), per, per)
+        orc.append_unique(cand)
+        if step % 5 == 4:
+            new = rng.choice(pool, int(rng.integers(1, 9))).astype(np.int32)
+            B.nanospec_vocab_update(st.h, dev(new), [0, len(new)])
+            orc.update(new)
+    assert np.array_equal(st.read_active()[0], orc.active())
+    assert B.nanospec_last_device_error(st.h) == 0
+    st.close()
+
+
 def _small_state(V=1000, d=64, batch=1, window=8, topk_cap=4, m_cap=3, k_cap=64):
     return B.State(V, d, batch, window, topk_cap, m_cap, k_cap)
 

@@ -69,6 +69,11 @@ def main():
     from paper_2605_26444_amd import synth
 
     torch.cuda.set_device(0)
+
+    def log(msg):
+        """one line per finished leg on stderr (under a profiler a leg can take minutes)"""
+        print(f"bench: {msg} [{time.time() - t_start:.1f} s]", file=sys.stderr, flush=True)
+    t_start = time.time()
     cfg = dict(synth.CONFIGS[args.config])
     K, Wm = args.steps, args.warmup
     if K < 1 or Wm < 0:
@@ -190,6 +195,7 @@ def main():
     ms, ms_all = timed(step, Wm, K, reset=reset_main)
     n_active = [len(a) for a in st.read_active()]
     n_sum = int(np.sum(n_active))
+    log("step loop timed")
 
     # roofline leg: the sparse-head kernel alone, same launch configuration, cold rotation, HIP events
     # on the launch stream around a back-to-back train of launches (no host work in between).
@@ -197,6 +203,7 @@ def main():
     head = lambda i, r, cs: B.nanospec_sparse_head(st.h, Wd[r % R], Hd[r % NH], M, logits, cs)
     head_us = timed(head, 0, NL)[0] * 1e3 / NL
     alg_bytes = n_sum * d * 2                                  # gathered weight bytes per launch
+    log("head alone timed")
     achieved = alg_bytes / (head_us * 1e-6) / 1e9
 
     def train(fn, n=200, reset=None):
@@ -234,6 +241,7 @@ def main():
     upd_us = timed(upd_only, 0, total_steps, reset=lambda: B.nanospec_vocab_init(st_u.h, d_ctx, coff, d_T0, toff, stream))[0] * 1e3 / total_steps
     st_u.close()
     topk_us = train(lambda i, r, cs: B.nanospec_topk_remap(st.h, logits, M, k, out_ids, out_vals, cs))
+    log("cold check, update and selection timed")
 
     # What one launch of this size can reach on this chip: read-only kernels that move the head's bytes and
     # compute nothing -- the same rows through the same id list, the same number of bytes contiguously, and the
@@ -331,6 +339,7 @@ def main():
         for q in pst:
             q.close()
 
+    log("ceilings and packed-buffer variant timed")
     # the one-off stream initialisation (S(0) = context, T = T0; clear + apply kernels), on a scratch state
     st_i = B.State(V, d, Bn, seqs["window"], seqs["topk_cap"], M, k)
     init_us = train(lambda i, r, cs: B.nanospec_vocab_init(st_i.h, d_ctx, coff, d_T0, toff, cs), 16)
@@ -356,6 +365,7 @@ def main():
     closed = {"steps_per_s": round(KL / (loop_ms * 1e-3), 1), "us_per_step": round(loop_ms * 1e3 / KL, 2),
               "append_unique_us": round(app_us, 2), "topk_logprob_us": round(lp_us, 2), "active_after": n_loop[0]}
 
+    log("closed loop timed")
     # The two readings of the vocabulary side by side (Eq. 4 window over the raw stream against the first-in
     # first-out queue of distinct ids of Sec. 3.3 / the appendix): the same context and the same appended ids on
     # two fresh states, |active| afterwards and the time per update over a graph of the real updates.
@@ -372,6 +382,7 @@ def main():
                                 "update_us": round(us, 2)}
         st2.close()
 
+    log("vocabulary policies timed")
     # dense comparison point: full-vocabulary head + top-k over V.  The ratio that is reported takes the faster
     # of this library's dense head and the vendor GEMM library on the same product (bf16 out, through
     # torch.matmul, timed eagerly) as the dense head.
@@ -409,6 +420,7 @@ def main():
                  "speedup_step_own_dense_kernels": round(dense_us / step_us, 2),
                  "speedup_head": round(min(dense_head_us, lib_us) / head_us, 2)}
 
+    log("dense comparison timed")
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(cfg, seqs, W_host, synth)

@@ -254,7 +254,11 @@ def main():
         s_us = train(lambda i, r, cs: B.nanospec_calib_stream_read(Wd[r % R], nb, sink, cs), 240)
         full = V * d * 2
         f_us = train(lambda i, r, cs: B.nanospec_calib_stream_read(Wd[r % R], full, sink, cs), 32)
-        ceilings = {"gather_same_rows_us": round(g_us, 2), "gather_same_rows_GBps": round(alg_bytes / g_us / 1e3, 1),
+        v_us = None
+        if M <= 8 and d in (2048, 4096):            # the same head on the vector ALUs (unpack + FMA), for comparison
+            vl = torch.empty((1, M, cap), dtype=torch.float32, device="cuda")
+            v_us = round(train(lambda i, r, cs: B.nanospec_calib_valu_head(st.h, Wd[r % R], Hd[r % NH], M, vl, cs), 240), 2)
+        ceilings = {"vector_alu_head_us": v_us, "gather_same_rows_us": round(g_us, 2), "gather_same_rows_GBps": round(alg_bytes / g_us / 1e3, 1),
                     "stream_same_bytes_us": round(s_us, 2), "stream_same_bytes_GBps": round(nb / s_us / 1e3, 1),
                     "stream_whole_matrix_GBps": round(full / f_us / 1e3, 1),
                     "head_over_gather": round(head_us / g_us, 3)}

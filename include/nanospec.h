@@ -260,7 +260,15 @@ NANOSPEC_API nanospec_status nanospec_dense_topk_static(const float* d_logits, i
  *   nanospec_calib_gather_read : reads the d bf16 of every row W[ids_b[j]], j < n_b, of sequence 0 of the
  *                                state's active list (the rows nanospec_sparse_head would gather).
  *   d_sink : device scratch of at least 1024 bytes (written practically never).
+ *   nanospec_calib_valu_head   : the sparse head of one sequence (Eq. 1 on the active rows) computed on the
+ *                                vector ALUs (unpack + fused multiply-add) instead of the matrix cores, with the
+ *                                workgroup shape and loads of the product kernel for M <= 8: the measurement
+ *                                behind the choice of the matrix cores below 16 hidden rows.  Logits as
+ *                                nanospec_sparse_head (same layout and tolerance; the summation order differs).
+ *                                batch == 1, M <= 8, d = 2048 or 4096, else EINVAL.
  * Errors: EINVAL (null, sizes < 1, bytes % 16 != 0).  Asynchronous. */
+NANOSPEC_API nanospec_status nanospec_calib_valu_head(nanospec_state* st, const void* d_W_bf16, const void* d_H_bf16, int32_t M,
+                                                      float* d_logits, void* hip_stream);
 NANOSPEC_API nanospec_status nanospec_calib_stream_read(const void* d_buf, int64_t bytes, void* d_sink, void* hip_stream);
 NANOSPEC_API nanospec_status nanospec_calib_gather_read(nanospec_state* st, const void* d_W_bf16, void* d_sink,
                                                         void* hip_stream);

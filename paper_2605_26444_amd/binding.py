@@ -26,7 +26,7 @@ EXPORTS = [
     "nanospec_topk_remap", "nanospec_topk_logprob_remap", "nanospec_dense_head", "nanospec_dense_topk_workspace", "nanospec_dense_topk",
     "nanospec_dense_topk_static_limit", "nanospec_dense_topk_static",
     "nanospec_packed_bytes", "nanospec_packed_enable", "nanospec_packed_gather", "nanospec_packed_head", "nanospec_packed_view",
-    "nanospec_calib_stream_read", "nanospec_calib_gather_read", "nanospec_last_device_error",
+    "nanospec_calib_stream_read", "nanospec_calib_gather_read", "nanospec_calib_valu_head", "nanospec_last_device_error",
 ]
 
 
@@ -70,6 +70,7 @@ def lib() -> C.CDLL:
         L.nanospec_topk_logprob_remap.argtypes = [vp, vp, i32, i32, vp, vp, vp]
         L.nanospec_calib_stream_read.argtypes = [vp, i64, vp, vp]
         L.nanospec_calib_gather_read.argtypes = [vp, vp, vp, vp]
+        L.nanospec_calib_valu_head.argtypes = [vp, vp, vp, i32, vp, vp]
         L.nanospec_dense_head.argtypes = [vp, vp, i32, i32, i32, vp, vp]
         L.nanospec_dense_topk_workspace.restype = i64
         L.nanospec_dense_topk_workspace.argtypes = [i32, i32, i32]
@@ -192,6 +193,10 @@ def nanospec_calib_stream_read(d_buf, nbytes, d_sink, stream=None):
 
 def nanospec_calib_gather_read(st, d_W, d_sink, stream=None):
     _check(lib().nanospec_calib_gather_read(st, _ptr(d_W), _ptr(d_sink), _stream(stream)), "nanospec_calib_gather_read")
+
+
+def nanospec_calib_valu_head(st, d_W, d_H, M, d_logits, stream=None):
+    _check(lib().nanospec_calib_valu_head(st, _ptr(d_W), _ptr(d_H), M, _ptr(d_logits), _stream(stream)), "nanospec_calib_valu_head")
 
 
 def nanospec_dense_head(d_W, d_H, V, d, M_total, d_logits, stream=None):

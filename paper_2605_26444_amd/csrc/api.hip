@@ -73,6 +73,7 @@ hipError_t ensure_device_configured() {
   if (g_cfg_done[dev]) return hipSuccess;
   e = head_configure_device();
   if (e == hipSuccess) e = vocab_configure_device();
+  if (e == hipSuccess) e = calib_configure_device();
   if (e == hipSuccess) g_cfg_done[dev] = true;
   return e;
 }
@@ -350,6 +351,16 @@ nanospec_status nanospec_calib_gather_read(nanospec_state* st, const void* d_W_b
   if (!st || !d_W_bf16 || !d_sink || wrong_device(st)) return NANOSPEC_EINVAL;
   return launch_calib_gather(d_W_bf16, st->V, st->d, st->vp.ids, st->vp.n, st->vp.cap, d_sink,
                              static_cast<hipStream_t>(hip_stream)) == hipSuccess
+             ? NANOSPEC_OK
+             : NANOSPEC_EHIP;
+}
+
+nanospec_status nanospec_calib_valu_head(nanospec_state* st, const void* d_W_bf16, const void* d_H_bf16, int32_t M, float* d_logits,
+                                         void* hip_stream) {
+  if (!st || !d_W_bf16 || !d_H_bf16 || !d_logits || M < 1 || M > 8 || st->batch != 1 || (st->d != 2048 && st->d != 4096) || wrong_device(st))
+    return NANOSPEC_EINVAL;
+  return launch_calib_valu_head(d_W_bf16, d_H_bf16, st->V, st->d, M, st->vp.ids, st->vp.n, st->vp.cap, d_logits,
+                                static_cast<hipStream_t>(hip_stream)) == hipSuccess
              ? NANOSPEC_OK
              : NANOSPEC_EHIP;
 }

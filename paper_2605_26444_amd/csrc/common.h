@@ -93,6 +93,9 @@ hipError_t launch_packed_gather(const nanospec_state* st, const void* W, hipStre
 
 // calib.hip
 hipError_t launch_calib_stream(const void* buf, int64_t bytes, void* sink, hipStream_t s);
+hipError_t launch_calib_valu_head(const void* W, const void* H, int32_t V, int32_t d, int32_t M, const int32_t* ids,
+                                  const int32_t* n_dev, int32_t cap, float* logits, hipStream_t s);
+hipError_t calib_configure_device();
 hipError_t launch_calib_gather(const void* W, int32_t V, int32_t d, const int32_t* ids, const int32_t* n_dev, int32_t cap,
                                void* sink, hipStream_t s);
 

@@ -714,6 +714,25 @@ def test_prefill_stream_initialisation_on_device(window):
     st.close()
 
 
+@pytest.mark.parametrize("d,M,n_ctx", [(4096, 8, 3001), (4096, 5, 777), (2048, 8, 1500), (2048, 1, 40)])
+def test_vector_alu_head_against_oracle(d, M, n_ctx):
+    """the measurement-aid form of the head on the vector ALUs computes Eq. 1 on the active rows too"""
+    V = 20000
+    W = synth.normal_bf16(990 + d, 0, (V, d), 0.02)
+    H = synth.normal_bf16(991 + d, M, (1, M, d), 1.0, threads=1)
+    st = B.State(V, d, 1, n_ctx, 0, 8, 4)
+    rng = np.random.default_rng(d + M)
+    ctx = rng.choice(V, size=n_ctx, replace=False).astype(np.int32)
+    B.nanospec_vocab_init(st.h, dev(ctx), [0, n_ctx], None, [0, 0])
+    logits = torch.full((1, M, st.capacity), float("nan"), dtype=torch.float32, device="cuda")
+    B.nanospec_calib_valu_head(st.h, dev_bf16(W), dev_bf16(H), M, logits)
+    torch.cuda.synchronize()
+    act = st.read_active()[0]
+    o32, o64 = oracle.head(W, H[0], ids=act, omp=True)
+    assert_logits_close(logits.cpu().numpy()[0, :, :len(act)], o64, o32, f"vector-ALU head d={d} M={M}")
+    st.close()
+
+
 def test_calibration_reads_run_and_touch_nothing():
     """the measurement aids only read: they return OK, leave the state and their inputs unchanged."""
     V, d = 2000, 512

@@ -206,5 +206,30 @@ def topk_logprob(vals, ids, k: int):
     return oi, out
 
 
+def shared_rows(actives, min_share: int, shared_cap: int):
+    """Split of the active sets of several sequences into rows worth fetching once for the whole batch and rows
+    handled per sequence (multi-sequence serving; Sec. 4.6 states only that the per-sequence cost adds up over the
+    batch).  An id is *shared* when at least ``min_share`` of the sets hold it; only the ``shared_cap`` lowest such
+    ids count.  Returns (shared ids ascending int32[P],
+    pos int32[B][P] = position of shared id p in sequence b's ascending active list or -1 if b does not hold it,
+    rest = per sequence (ids int32[], positions int32[]) of its active ids that are not shared, ascending).
+    Written as the definition: a count per id over the sets, a threshold, list look-ups."""
+    count: dict[int, int] = {}
+    for a in actives:
+        for t in a:
+            count[int(t)] = count.get(int(t), 0) + 1
+    shared = sorted(t for t, c in count.items() if c >= min_share)[:max(shared_cap, 0)]
+    member = set(shared)
+    pos = np.full((len(actives), len(shared)), -1, dtype=np.int32)
+    rest = []
+    for b, a in enumerate(actives):
+        where = {int(t): j for j, t in enumerate(a)}
+        for p, t in enumerate(shared):
+            pos[b, p] = where.get(t, -1)
+        keep = [j for j, t in enumerate(a) if int(t) not in member]
+        rest.append((np.asarray([a[j] for j in keep], dtype=np.int32), np.asarray(keep, dtype=np.int32)))
+    return np.asarray(shared, dtype=np.int32), pos, rest
+
+
 def max_threads() -> int:
     return int(_lib(True).oracle_max_threads())

@@ -274,3 +274,52 @@ def test_fifo_invariants():
     a.append_unique([9, 7, 7, -1, 2, 300, 8, 6])
     b.update([6, 7, 8, 9])
     assert np.array_equal(a.active(), b.active()) and a.active().tolist() == [3, 6, 7, 8, 9]
+
+
+# ---- split of several sequences' active sets into shared rows and per-sequence rows -------------------------
+def test_shared_rows_hand_worked():
+    """Three sets over ids 0..9, worked by hand: 2 and 7 are in all three, 4 in two, the others in one."""
+    A = [np.array([1, 2, 4, 7], np.int32), np.array([2, 4, 7, 9], np.int32), np.array([0, 2, 7], np.int32)]
+    sh, pos, rest = oracle.shared_rows(A, 3, 10)
+    assert sh.tolist() == [2, 7]
+    assert pos.tolist() == [[1, 3], [0, 2], [1, 2]]
+    assert [r[0].tolist() for r in rest] == [[1, 4], [4, 9], [0]]
+    assert [r[1].tolist() for r in rest] == [[0, 2], [1, 3], [0]]
+    sh, pos, rest = oracle.shared_rows(A, 2, 10)                      # 4 joins; sequence 2 does not hold it
+    assert sh.tolist() == [2, 4, 7]
+    assert pos.tolist() == [[1, 2, 3], [0, 1, 2], [1, -1, 2]]
+    assert [r[0].tolist() for r in rest] == [[1], [9], [0]]
+    sh, pos, rest = oracle.shared_rows(A, 2, 2)                       # room for two shared rows only: 7 stays per sequence
+    assert sh.tolist() == [2, 4]
+    assert [r[0].tolist() for r in rest] == [[1, 7], [7, 9], [0, 7]]
+    assert [r[1].tolist() for r in rest] == [[0, 3], [2, 3], [0, 2]]
+    sh, pos, rest = oracle.shared_rows(A, 1, 0)                       # no room at all: everything per sequence
+    assert len(sh) == 0 and pos.shape == (3, 0) and [r[0].tolist() for r in rest] == [a.tolist() for a in A]
+
+
+def test_shared_rows_partition_every_pair_exactly_once():
+    """Property on random sets: every (sequence, active id) pair is covered by exactly one of the two parts, at the
+    id's own position; shared ids meet the threshold (counted here with a dense 0/1 matrix, not the oracle's dict)."""
+    rng = np.random.default_rng(11)
+    for trial in range(40):
+        V, B = int(rng.integers(5, 60)), int(rng.integers(1, 9))
+        A = [np.flatnonzero(rng.random(V) < rng.uniform(0.1, 0.9)).astype(np.int32) for _ in range(B)]
+        share, capP = int(rng.integers(1, B + 1)), int(rng.integers(0, V + 1))
+        sh, pos, rest = oracle.shared_rows(A, share, capP)
+        Mx = np.zeros((B, V), int)
+        for b, a in enumerate(A):
+            Mx[b, a] = 1
+        want = np.flatnonzero(Mx.sum(0) >= share)[:capP]
+        assert np.array_equal(sh, want)
+        for b, a in enumerate(A):
+            cover = np.zeros(len(a), int)
+            for p, t in enumerate(sh):
+                if pos[b, p] >= 0:
+                    assert a[pos[b, p]] == t
+                    cover[pos[b, p]] += 1
+                else:
+                    assert t not in a
+            ids_r, pos_r = rest[b]
+            assert np.array_equal(a[pos_r], ids_r) and np.all(np.diff(pos_r) > 0)
+            cover[pos_r] += 1
+            assert np.all(cover == 1)

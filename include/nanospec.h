@@ -205,6 +205,38 @@ NANOSPEC_API nanospec_status nanospec_packed_head(nanospec_state* st, const void
 NANOSPEC_API nanospec_status nanospec_packed_view(const nanospec_state* st, const void** d_buf, const int32_t** d_slot_id,
                                                   const int32_t** d_out_pos, const int32_t** d_counts);
 
+/* Several sequences in one state (multi-sequence serving; Sec. 4.6 states only that the method's per-sequence cost
+ * adds up over the batch): sequences drawing from one token distribution hold many of the same ids, and
+ * nanospec_sparse_head fetches such a row once per sequence.  The batch-union head splits the active sets: an id
+ * held by at least `min_share` of the sequences is a shared row -- listed once, fetched once, multiplied with the
+ * hidden rows of all sequences --, every other id stays on a per-sequence list and is handled as before.  Every
+ * (sequence, active id) pair is covered by exactly one part and its logit lands in the column the id has in that
+ * sequence's ascending active list: the logits have the layout of nanospec_sparse_head (a sequence that lacks a
+ * shared row has no column for it) and nanospec_topk_remap / nanospec_topk_logprob_remap apply unchanged.
+ *   nanospec_union_bytes  : device bytes nanospec_union_enable allocates for the given shared_cap (-1: bad argument).
+ *   nanospec_union_enable : allocate and clear the lists.  min_share: 0 = max(2, batch/8).  shared_cap: room on the
+ *                           shared list, a multiple of 64 in [64, capacity], 0 = capacity; when more ids qualify the
+ *                           lowest shared_cap are shared and the others stay per sequence.  Synchronous; once per
+ *                           state.  Errors: EINVAL (bad arguments, already enabled), ENOMEM, EHIP.
+ *   nanospec_union_build  : rebuild the lists from the current vocabulary state (two launches); call after every
+ *                           vocabulary call and before nanospec_union_head; it needs no hidden states, so it may run
+ *                           beside the draft backbone.  Asynchronous.  Errors: EINVAL (not enabled), EHIP.
+ *   nanospec_union_head   : d_logits fp32 [batch][M][capacity] as nanospec_sparse_head (entries j >= n_b
+ *                           unspecified), from d_W_bf16 [V][d] and d_H_bf16 [batch][M][d].  Asynchronous.
+ *                           Errors: EINVAL, ECAPACITY (M > m_cap).
+ *   nanospec_union_view   : borrowed device views for inspection: shared ids [shared_cap] and their number
+ *                           (first entry of d_shared_n), shared_pos [batch][shared_cap] (column or -1), rest ids
+ *                           and columns [batch][capacity], rest_n [batch]; any pointer may be NULL. */
+NANOSPEC_API int64_t nanospec_union_bytes(const nanospec_state* st, int32_t shared_cap);
+NANOSPEC_API nanospec_status nanospec_union_enable(nanospec_state* st, int32_t min_share, int32_t shared_cap);
+NANOSPEC_API nanospec_status nanospec_union_build(nanospec_state* st, void* hip_stream);
+NANOSPEC_API nanospec_status nanospec_union_head(nanospec_state* st, const void* d_W_bf16, const void* d_H_bf16, int32_t M,
+                                                 float* d_logits, void* hip_stream);
+NANOSPEC_API nanospec_status nanospec_union_view(const nanospec_state* st, const int32_t** d_shared_ids, const int32_t** d_shared_n,
+                                                 const int32_t** d_shared_pos, const int32_t** d_rest_ids,
+                                                 const int32_t** d_rest_pos, const int32_t** d_rest_n, int32_t* shared_cap,
+                                                 int32_t* min_share);
+
 /* Draft-token selection, SelectDraftTokens(z', I) of Alg. 1 with the operator T_K of Sec. 3.2:
  * for every (b, m) the k largest of logits[b][m][0..n_b), ordered by value descending then global
  * id ascending (+0 and -0 tie), written as global ids and values.  Slots beyond n_b get id -1

@@ -26,6 +26,7 @@ EXPORTS = [
     "nanospec_topk_remap", "nanospec_topk_logprob_remap", "nanospec_dense_head", "nanospec_dense_topk_workspace", "nanospec_dense_topk",
     "nanospec_dense_topk_static_limit", "nanospec_dense_topk_static",
     "nanospec_packed_bytes", "nanospec_packed_enable", "nanospec_packed_gather", "nanospec_packed_head", "nanospec_packed_view",
+    "nanospec_union_bytes", "nanospec_union_enable", "nanospec_union_build", "nanospec_union_head", "nanospec_union_view",
     "nanospec_calib_stream_read", "nanospec_calib_gather_read", "nanospec_calib_valu_head", "nanospec_last_device_error",
 ]
 
@@ -84,10 +85,16 @@ def lib() -> C.CDLL:
         L.nanospec_packed_gather.argtypes = [vp, vp, vp]
         L.nanospec_packed_head.argtypes = [vp, vp, i32, vp, vp]
         L.nanospec_packed_view.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp)]
+        L.nanospec_union_bytes.restype = i64
+        L.nanospec_union_bytes.argtypes = [vp, i32]
+        L.nanospec_union_enable.argtypes = [vp, i32, i32]
+        L.nanospec_union_build.argtypes = [vp, vp]
+        L.nanospec_union_head.argtypes = [vp, vp, vp, i32, vp, vp]
+        L.nanospec_union_view.argtypes = [vp] + [C.POINTER(vp)] * 6 + [i32p, i32p]
         L.nanospec_last_device_error.argtypes = [vp, i32p, vp]
         for name in EXPORTS:
             if name not in ("nanospec_status_string", "nanospec_dense_topk_workspace", "nanospec_dense_topk_static_limit",
-                            "nanospec_packed_bytes"):
+                            "nanospec_packed_bytes", "nanospec_union_bytes"):
                 getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -245,6 +252,30 @@ def nanospec_packed_view(st):
     return a.value, b.value, c.value, d.value
 
 
+def nanospec_union_bytes(st, shared_cap=0) -> int:
+    return int(lib().nanospec_union_bytes(st, shared_cap))
+
+
+def nanospec_union_enable(st, min_share=0, shared_cap=0):
+    _check(lib().nanospec_union_enable(st, min_share, shared_cap), "nanospec_union_enable")
+
+
+def nanospec_union_build(st, stream=None):
+    _check(lib().nanospec_union_build(st, _stream(stream)), "nanospec_union_build")
+
+
+def nanospec_union_head(st, d_W, d_H, M, d_logits, stream=None):
+    _check(lib().nanospec_union_head(st, _ptr(d_W), _ptr(d_H), M, _ptr(d_logits), _stream(stream)), "nanospec_union_head")
+
+
+def nanospec_union_view(st):
+    """(shared_ids, shared_n, shared_pos, rest_ids, rest_pos, rest_n: raw device addresses; shared_cap, min_share)."""
+    ptrs = [C.c_void_p() for _ in range(6)]
+    cap, share = C.c_int32(), C.c_int32()
+    _check(lib().nanospec_union_view(st, *[C.byref(x) for x in ptrs], C.byref(cap), C.byref(share)), "nanospec_union_view")
+    return tuple(x.value for x in ptrs) + (cap.value, share.value)
+
+
 def nanospec_last_device_error(st, stream=None) -> int:
     f = C.c_int32()
     _check(lib().nanospec_last_device_error(st, C.byref(f), _stream(stream)), "nanospec_last_device_error")
@@ -279,6 +310,20 @@ class State:
         c = _copy_from_device(cnt, 2, np.int32)
         return (_copy_from_device(sid, self.capacity, np.int32), _copy_from_device(pos, self.capacity, np.int32), int(c[0]), int(c[1]),
                 _copy_from_device(buf, self.capacity * self.d, np.uint16).reshape(self.capacity, self.d))
+
+    def read_union(self):
+        """host copies of the batch-union lists: (shared ids int32[P], shared_pos int32[batch][P],
+        [(rest ids, rest columns) per sequence], min_share, shared_cap)."""
+        import torch
+        torch.cuda.synchronize()
+        sid, sn, spos, rid, rpos, rn, cap, share = nanospec_union_view(self.h)
+        P = int(_copy_from_device(sn, 1, np.int32)[0])
+        ids = _copy_from_device(sid, cap, np.int32)[:P]
+        pos = _copy_from_device(spos, self.batch * cap, np.int32).reshape(self.batch, cap)[:, :P]
+        n = _copy_from_device(rn, self.batch, np.int32)
+        ri = _copy_from_device(rid, self.batch * self.capacity, np.int32).reshape(self.batch, self.capacity)
+        rp = _copy_from_device(rpos, self.batch * self.capacity, np.int32).reshape(self.batch, self.capacity)
+        return ids, pos, [(ri[b, :n[b]].copy(), rp[b, :n[b]].copy()) for b in range(self.batch)], share, cap
 
     def read_active(self):
         """copy the active id lists back to the host: list of int32 arrays (one per sequence)."""

@@ -74,6 +74,7 @@ hipError_t ensure_device_configured() {
   e = head_configure_device();
   if (e == hipSuccess) e = vocab_configure_device();
   if (e == hipSuccess) e = calib_configure_device();
+  if (e == hipSuccess) e = union_configure_device();
   if (e == hipSuccess) g_cfg_done[dev] = true;
   return e;
 }
@@ -185,6 +186,7 @@ nanospec_status nanospec_create(nanospec_state** out, int32_t V, int32_t d, int3
 nanospec_status nanospec_destroy(nanospec_state* st) {
   if (!st) return NANOSPEC_EINVAL;
   if (st->pk_base) (void)hipFree(st->pk_base);
+  if (st->un_base) (void)hipFree(st->un_base);
   hipError_t e1 = hipFree(st->base);
   hipError_t e2 = hipHostFree(st->h_err_pinned);
   delete st;
@@ -250,6 +252,90 @@ nanospec_status nanospec_packed_view(const nanospec_state* st, const void** d_bu
   if (d_slot_id) *d_slot_id = st->pk.slot_id;
   if (d_out_pos) *d_out_pos = st->pk.out_pos;
   if (d_counts) *d_counts = st->pk.scal;
+  return NANOSPEC_OK;
+}
+
+int64_t nanospec_union_bytes(const nanospec_state* st, int32_t shared_cap) {
+  if (!st) return -1;
+  const int64_t cap = st->vp.cap, nw = st->vp.nwords, B = st->batch;
+  if (shared_cap == 0) shared_cap = (int32_t)cap;
+  if (shared_cap < 64 || shared_cap % 64 != 0 || shared_cap > cap) return -1;
+  const int64_t groups = (B * st->m_cap + 63) / 64;
+  return 2 * round_up(nw * 4, 256) + round_up((int64_t)shared_cap * 4, 256) + round_up(groups * 4, 256) +
+         round_up(B * shared_cap * 4, 256) + 2 * round_up(B * cap * 4, 256) + round_up(B * 4, 256);
+}
+
+nanospec_status nanospec_union_enable(nanospec_state* st, int32_t min_share, int32_t shared_cap) {
+  if (!st || wrong_device(st) || min_share < 0) return NANOSPEC_EINVAL;
+  if (st->un_base) return NANOSPEC_EINVAL;                 // thresholds are fixed once enabled
+  const int64_t cap = st->vp.cap, nw = st->vp.nwords, B = st->batch;
+  if (shared_cap == 0) shared_cap = (int32_t)cap;
+  if (min_share == 0) min_share = B / 8 > 2 ? (int32_t)(B / 8) : 2;
+  const int64_t bytes = nanospec_union_bytes(st, shared_cap);
+  if (bytes < 0) return NANOSPEC_EINVAL;
+  char* base = nullptr;
+  if (hipMalloc(reinterpret_cast<void**>(&base), bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    return NANOSPEC_ENOMEM;
+  }
+  char* p = base;
+  auto take = [&](int64_t b) { char* r = p; p += round_up(b, 256); return r; };
+  UnionPtrs& u = st->un;
+  st->un_groups = (int32_t)((B * st->m_cap + 63) / 64);
+  u.shared_cap = shared_cap;
+  u.min_share = min_share;
+  u.shared_bits = reinterpret_cast<uint32_t*>(take(nw * 4));
+  u.shared_cnt = reinterpret_cast<int32_t*>(take(nw * 4));
+  u.shared_ids = reinterpret_cast<int32_t*>(take((int64_t)shared_cap * 4));
+  u.shared_n = reinterpret_cast<int32_t*>(take((int64_t)st->un_groups * 4));
+  u.shared_pos = reinterpret_cast<int32_t*>(take(B * shared_cap * 4));
+  u.rest_ids = reinterpret_cast<int32_t*>(take(B * cap * 4));
+  u.rest_pos = reinterpret_cast<int32_t*>(take(B * cap * 4));
+  u.rest_n = reinterpret_cast<int32_t*>(take(B * 4));
+  st->un_base = base;
+  if (p - base > bytes || launch_union_reset(st, nullptr) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipFree(base);
+    st->un_base = nullptr;
+    return NANOSPEC_EHIP;
+  }
+  return NANOSPEC_OK;
+}
+
+nanospec_status nanospec_union_build(nanospec_state* st, void* hip_stream) {
+  if (!st || wrong_device(st) || !st->un_base) return NANOSPEC_EINVAL;
+  return launch_union_build(st, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;
+}
+
+nanospec_status nanospec_union_head(nanospec_state* st, const void* d_W_bf16, const void* d_H_bf16, int32_t M, float* d_logits,
+                                    void* hip_stream) {
+  if (!st || !d_W_bf16 || !d_H_bf16 || !d_logits || M < 1 || wrong_device(st) || !st->un_base) return NANOSPEC_EINVAL;
+  if (M > st->m_cap) return NANOSPEC_ECAPACITY;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const UnionPtrs& u = st->un;
+  const int32_t cap = st->vp.cap;
+  // shared rows: fetched once, multiplied with every sequence's hidden rows, scattered to each sequence's columns
+  hipError_t e = launch_head_shared(d_W_bf16, d_H_bf16, u.shared_ids, u.shared_n, u.shared_cap, st->V, st->batch * M, M, st->d, cap,
+                                    d_logits, u.shared_pos, u.shared_cap, s);
+  // the rest per sequence, exactly as nanospec_sparse_head but on the shorter lists
+  if (e == hipSuccess)
+    e = launch_head(d_W_bf16, d_H_bf16, u.rest_ids, u.rest_n, 0, cap, st->V, st->batch, M, st->d, cap, cap, d_logits, st->partial,
+                    st->partial_bytes, u.rest_pos, s);
+  return e == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;
+}
+
+nanospec_status nanospec_union_view(const nanospec_state* st, const int32_t** d_shared_ids, const int32_t** d_shared_n,
+                                    const int32_t** d_shared_pos, const int32_t** d_rest_ids, const int32_t** d_rest_pos,
+                                    const int32_t** d_rest_n, int32_t* shared_cap, int32_t* min_share) {
+  if (!st || !st->un_base) return NANOSPEC_EINVAL;
+  if (d_shared_ids) *d_shared_ids = st->un.shared_ids;
+  if (d_shared_n) *d_shared_n = st->un.shared_n;
+  if (d_shared_pos) *d_shared_pos = st->un.shared_pos;
+  if (d_rest_ids) *d_rest_ids = st->un.rest_ids;
+  if (d_rest_pos) *d_rest_pos = st->un.rest_pos;
+  if (d_rest_n) *d_rest_n = st->un.rest_n;
+  if (shared_cap) *shared_cap = st->un.shared_cap;
+  if (min_share) *min_share = st->un.min_share;
   return NANOSPEC_OK;
 }
 

@@ -43,6 +43,19 @@ struct PackedPtrs {
   int32_t cap;
 };
 
+// Batch-union head (several sequences): rows shared by many sequences, and what is left per sequence.
+struct UnionPtrs {
+  uint32_t* shared_bits;  // [nwords] bit = id held by at least min_share sequences
+  int32_t* shared_cnt;    // [nwords] set bits per word
+  int32_t* shared_ids;    // [shared_cap] the lowest shared_cap such ids, ascending
+  int32_t* shared_n;      // [groups] their number, repeated once per group of 64 hidden rows
+  int32_t* shared_pos;    // [batch][shared_cap] column of shared row r in the sequence's logits, -1 if the sequence lacks it
+  int32_t* rest_ids;      // [batch][cap] the sequence's other active ids, ascending
+  int32_t* rest_pos;      // [batch][cap] their columns
+  int32_t* rest_n;        // [batch]
+  int32_t shared_cap, min_share;
+};
+
 }  // namespace nanospec
 
 struct nanospec_state {
@@ -59,6 +72,9 @@ struct nanospec_state {
   int32_t policy, policy_next;   // vocabulary reading in force / chosen for the next init
   nanospec::PackedPtrs pk;       // packed-buffer variant; pk.buf == nullptr until nanospec_packed_enable
   char* pk_base;                 // its one device allocation
+  nanospec::UnionPtrs un;        // batch-union head; un_base == nullptr until nanospec_union_enable
+  char* un_base;
+  int32_t un_groups;             // groups of 64 hidden rows at M = m_cap
 };
 
 namespace nanospec {
@@ -80,6 +96,16 @@ hipError_t launch_head(const void* W, const void* H, const int32_t* ids, const i
                        int32_t cap_rows, int32_t V, int32_t batch, int32_t M, int32_t d, int64_t ld_logits,
                        int64_t ids_stride, float* logits, float* partial, int64_t partial_bytes, const int32_t* opos,
                        hipStream_t s);
+
+// every row of one list against rows_total hidden rows of several sequences (seq_rows each); columns per sequence
+hipError_t launch_head_shared(const void* W, const void* H, const int32_t* ids, const int32_t* n_rep, int32_t cap_rows, int32_t V,
+                              int32_t rows_total, int32_t seq_rows, int32_t d, int64_t ld_logits, float* logits, const int32_t* opos,
+                              int64_t opos_stride, hipStream_t s);
+
+// union.hip
+hipError_t union_configure_device();
+hipError_t launch_union_reset(const nanospec_state* st, hipStream_t s);
+hipError_t launch_union_build(const nanospec_state* st, hipStream_t s);
 
 // topk.hip
 int64_t topk_workspace_bytes(int32_t cap, int32_t rows, int32_t k);

@@ -477,7 +477,8 @@ template <int MT, bool LOOPK, int FAST>
 __global__ __launch_bounds__(256) void head_tile64_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
                                                           const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev,
                                                           int n_fixed, int V, int M, int d, int64_t ld, int64_t ids_stride,
-                                                          float* __restrict__ out, const int32_t* __restrict__ opos) {
+                                                          float* __restrict__ out, const int32_t* __restrict__ opos,
+                                                          int64_t opos_stride, int seq_rows, int row0) {
   constexpr int STRB = 1024 + kTilePad;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int b = blockIdx.z, batch = gridDim.z;
@@ -494,11 +495,14 @@ __global__ __launch_bounds__(256) void head_tile64_kernel(const uint16_t* __rest
   int vzero = 0;
   if (FAST) asm volatile("" : "+v"(vzero));               // keeps the row count's load on the vector path, in order behind the ids
   const int nv = n_dev ? n_dev[b + vzero] : n_fixed;
-  // rows kept in an order of their own (LOOPK only): the columns their logits go to, four per lane, asked for now
+  // rows kept in an order of their own (LOOPK only): the columns their logits go to, four per lane, asked for now.
+  // seq_rows > 0: the list is shared by several sequences of seq_rows hidden rows each and every sequence has
+  // its own columns -- hidden row r (counted from row0 on, over the whole launch) belongs to sequence r / seq_rows;
+  // those columns are fetched at the end, per hidden row.
   int4 jo4 = make_int4(0, 0, 0, 0);
-  if (LOOPK && opos) {
+  if (LOOPK && opos && seq_rows == 0) {
     const int jq = j0 + 4 * (lane >> 4);
-    jo4 = jq + 3 < (int)ids_stride ? *reinterpret_cast<const int4*>(opos + b * ids_stride + jq) : make_int4(-1, -1, -1, -1);
+    jo4 = jq + 3 < (int)opos_stride ? *reinterpret_cast<const int4*>(opos + b * opos_stride + jq) : make_int4(-1, -1, -1, -1);
   }
   u32x4 hv[16], wv[16];
   int n = nv;
@@ -552,9 +556,9 @@ __global__ __launch_bounds__(256) void head_tile64_kernel(const uint16_t* __rest
   // split-K launches are sized by capacity: tiles past n leave before they pull their hidden-row slice
   // (measured neutral at n close to capacity, and it spares the L2 when n is far below it); the FAST form
   // learns n only with the ids and leaves after its first slice's loads
-  if (!FAST && !LOOPK && (int)blockIdx.x * 64 >= n) return;
+  if (!FAST && n_dev && (int)blockIdx.x * 64 >= n) return;
   load_slice(s0);
-  if (FAST && !LOOPK && (int)blockIdx.x * 64 >= n) return;
+  if (FAST && n_dev && (int)blockIdx.x * 64 >= n) return;
   const int rd_off = (lane & 15) * STRB + (lane >> 4) * 16;
   f32x4 acc[MT];
 #pragma unroll
@@ -591,6 +595,9 @@ __global__ __launch_bounds__(256) void head_tile64_kernel(const uint16_t* __rest
                        : out + (((int64_t)blockIdx.y * batch + b) * M + m) * ld + j;   // ld = plane row stride
     if (LOOPK && opos) {
       float* rowp = out + ((int64_t)b * M + m) * ld;
+      if (seq_rows > 0)
+        jo4 = j + 3 < (int)opos_stride ? *reinterpret_cast<const int4*>(opos + (int64_t)((row0 + b * M + m) / seq_rows) * opos_stride + j)
+                                       : make_int4(-1, -1, -1, -1);
       const int jo[4] = {jo4.x, jo4.y, jo4.z, jo4.w};
 #pragma unroll
       for (int v = 0; v < 4; ++v)
@@ -645,9 +652,9 @@ static hipError_t run_splitk(const uint16_t* W, const uint16_t* H, const int32_t
   const int fast = d % 512 != 0 ? 0 : (M == 64 ? 2 : 1);   // 2: every wavefront's sixteen hidden rows exist
   hipError_t e;
   const dim3 grid((cap_rows + 63) / 64, S, batch);
-  if (fast == 2) head_tile64_kernel<MT, false, 2><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial, nullptr);
-  else if (fast == 1) head_tile64_kernel<MT, false, 1><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial, nullptr);
-  else head_tile64_kernel<MT, false, 0><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial, nullptr);
+  if (fast == 2) head_tile64_kernel<MT, false, 2><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial, nullptr, 0, 0, 0);
+  else if (fast == 1) head_tile64_kernel<MT, false, 1><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial, nullptr, 0, 0, 0);
+  else head_tile64_kernel<MT, false, 0><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, 0, V, M, d, cap_rows, ids_stride, partial, nullptr, 0, 0, 0);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   head_splitk_reduce_kernel<<<dim3((cap_rows / 4 + 255) / 256, M, batch), 256, 0, s>>>(partial, n_dev, S, M, cap_rows, ld,
@@ -662,9 +669,9 @@ static hipError_t run_tile64(const uint16_t* W, const uint16_t* H, const int32_t
   constexpr int LDS = 4 * 16 * (1024 + kTilePad);
   const int fast = d % 512 != 0 ? 0 : (M == 64 ? 2 : 1);   // 2: every wavefront's sixteen hidden rows exist
   const dim3 grid((cap_rows + 63) / 64, 1, batch);
-  if (fast == 2) head_tile64_kernel<MT, true, 2><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits, opos);
-  else if (fast == 1) head_tile64_kernel<MT, true, 1><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits, opos);
-  else head_tile64_kernel<MT, true, 0><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits, opos);
+  if (fast == 2) head_tile64_kernel<MT, true, 2><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits, opos, ids_stride, 0, 0);
+  else if (fast == 1) head_tile64_kernel<MT, true, 1><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits, opos, ids_stride, 0, 0);
+  else head_tile64_kernel<MT, true, 0><<<grid, 256, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, ids_stride, logits, opos, ids_stride, 0, 0);
   return hipGetLastError();
 }
 
@@ -696,6 +703,44 @@ static hipError_t launch_head_64(const uint16_t* W, const uint16_t* H, const int
   }
   if (M <= 32) return run_tile64<2>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
   return run_tile64<4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
+}
+
+// One row list shared by several sequences (rows that many sequences of a batch hold): every listed row is
+// multiplied with all rows_total hidden rows H[rows_total][d] (the sequences' hidden rows back to back, seq_rows
+// each), 64 hidden rows per launch group, and the logit of list row j for a hidden row of sequence q goes to
+// column opos[q * opos_stride + j] of that hidden row's logits row (nowhere if negative: q does not hold the row).
+// n_rep: the list length on the device, once per group (rows_total / 64 + 1 equal entries).  cap_rows % 64 == 0.
+template <int MT>
+static hipError_t run_shared(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_rep, int32_t cap_rows, int32_t V,
+                             int32_t groups, int32_t M, int32_t d, int64_t ld, float* logits, const int32_t* opos, int64_t opos_stride,
+                             int32_t seq_rows, int32_t row0, hipStream_t s) {
+  constexpr int LDS = 4 * 16 * (1024 + kTilePad);
+  const int fast = d % 512 != 0 ? 0 : (M == 64 ? 2 : 1);
+  const dim3 grid(cap_rows / 64, 1, groups);
+  if (fast == 2) head_tile64_kernel<MT, true, 2><<<grid, 256, LDS, s>>>(W, H, ids, n_rep, 0, V, M, d, ld, 0, logits, opos, opos_stride, seq_rows, row0);
+  else if (fast == 1) head_tile64_kernel<MT, true, 1><<<grid, 256, LDS, s>>>(W, H, ids, n_rep, 0, V, M, d, ld, 0, logits, opos, opos_stride, seq_rows, row0);
+  else head_tile64_kernel<MT, true, 0><<<grid, 256, LDS, s>>>(W, H, ids, n_rep, 0, V, M, d, ld, 0, logits, opos, opos_stride, seq_rows, row0);
+  return hipGetLastError();
+}
+
+hipError_t launch_head_shared(const void* W, const void* H, const int32_t* ids, const int32_t* n_rep, int32_t cap_rows, int32_t V,
+                              int32_t rows_total, int32_t seq_rows, int32_t d, int64_t ld_logits, float* logits, const int32_t* opos,
+                              int64_t opos_stride, hipStream_t s) {
+  const uint16_t* Wp = static_cast<const uint16_t*>(W);
+  const uint16_t* Hp = static_cast<const uint16_t*>(H);
+  if (cap_rows < 64 || cap_rows % 64 != 0 || opos_stride % 4 != 0 || seq_rows < 1 || rows_total < 1) return hipErrorInvalidValue;
+  const int groups = rows_total / 64, tail = rows_total % 64;
+  if (groups > 0) {
+    hipError_t e = run_shared<4>(Wp, Hp, ids, n_rep, cap_rows, V, groups, 64, d, ld_logits, logits, opos, opos_stride, seq_rows, 0, s);
+    if (e != hipSuccess) return e;
+  }
+  if (tail > 0) {                                           // the last, shorter group of hidden rows
+    const uint16_t* Ht = Hp + (int64_t)groups * 64 * d;
+    float* lt = logits + (int64_t)groups * 64 * ld_logits;
+    if (tail <= 32) return run_shared<2>(Wp, Ht, ids, n_rep, cap_rows, V, 1, tail, d, ld_logits, lt, opos, opos_stride, seq_rows, groups * 64, s);
+    return run_shared<4>(Wp, Ht, ids, n_rep, cap_rows, V, 1, tail, d, ld_logits, lt, opos, opos_stride, seq_rows, groups * 64, s);
+  }
+  return hipSuccess;
 }
 
 // The dynamic-LDS limit of a kernel is a per-device attribute of the function.  Every instantiation that may ask

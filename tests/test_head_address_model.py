@@ -141,6 +141,27 @@ def check_tile64(M, d, batch, cap, V, n, dense, MT, fast, split, S, partial_elem
             need(S * batch * M * cap <= partial_elems, "planes", S, batch, M, cap)
 
 
+def check_shared(rows_total, seq_rows, d, cap_rows, opos_stride, nseq=None):
+    """launch_head_shared: one id list for all sequences; hidden rows [rows_total][d] walked in groups of 64 (the last
+    one shorter), column tables [nseq][opos_stride] looked up per hidden row at the end."""
+    nseq = nseq if nseq is not None else ceil_div(rows_total, seq_rows)
+    need(cap_rows >= 64 and cap_rows % 64 == 0 and opos_stride % 4 == 0, "list capacity", cap_rows, opos_stride)
+    groups, tail = rows_total // 64, rows_total % 64
+    launches = ([(0, groups, 64)] if groups else []) + ([(groups * 64, 1, tail)] if tail else [])
+    for row0, nb, M in launches:
+        fast = 0 if d % 512 != 0 else (2 if M == 64 else 1)
+        check_tile64(M, d, nb, cap_rows, 1 << 30, cap_rows, False, MT=2 if M <= 32 else 4, fast=fast, split=False, S=ceil_div(d, 512))
+        for b in (0, nb - 1):
+            for m in range(M):                                 # rows the kernel stores for: m < M
+                r = row0 + b * M + m
+                need(r < rows_total, "hidden row", r, rows_total)
+                q = r // seq_rows
+                need(q < nseq, "sequence of a hidden row", q, nseq)
+                for j in range(0, cap_rows, 4):
+                    if j + 3 < opos_stride:                    # the kernel's own guard
+                        need(q * opos_stride + j + 3 < nseq * opos_stride, "column table", q, j)
+
+
 def check(M, d, batch, cap, V, n, dense):
     for variant, prm in plan(M, d, batch, cap, dense):
         if variant == "quad":
@@ -167,6 +188,16 @@ def test_every_selected_variant_stays_inside_its_buffers_sparse(d):
 def test_every_selected_variant_stays_inside_its_buffers_dense(V):
     for M, d in itertools.product((1, 4, 5, 8, 12, 16, 17, 32, 40, 64), (512, 520, 3584, 4096, 8192)):
         check(M, d, 1, V, V, V, dense=True)
+
+
+def test_shared_list_launches_stay_inside_their_buffers():
+    for nseq, seq_rows, d, cap_rows in itertools.product((1, 3, 6, 20, 30, 64), (1, 3, 5, 8, 16, 40), (64, 512, 1032, 4096), (64, 1472)):
+        check_shared(nseq * seq_rows, seq_rows, d, cap_rows, cap_rows)
+        check_shared(nseq * seq_rows, seq_rows, d, cap_rows, 64)          # a column table narrower than the list
+    with pytest.raises(OutOfBounds):                                       # hidden rows counted per launch, not over the whole batch
+        check_shared(160, 8, 4096, 64, 64, nseq=19)
+    with pytest.raises(OutOfBounds):
+        check_shared(160, 8, 4096, 96, 96)
 
 
 def test_the_selection_that_once_faulted_is_rejected():

@@ -57,6 +57,10 @@ def main():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-packed", action="store_true", help="skip the packed-buffer variant (the paper's own design)")
     ap.add_argument("--no-cold-check", action="store_true", help="skip timing the head over rotations of 16 / 32 / 48 weight copies")
+    ap.add_argument("--no-union", action="store_true", help="skip the batch-union head (several sequences only)")
+    ap.add_argument("--union-shares", default="2,4,8,16,32", help="min_share thresholds the batch-union leg sweeps")
+    ap.add_argument("--only-union", type=int, default=0, metavar="MIN_SHARE",
+                    help="run nothing but a train of nanospec_union_head launches at this threshold (for counter runs)")
     ap.add_argument("--traffic", default=None, help="HBM bytes per head launch from rocprofv3 --pmc runs (or omit)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -192,6 +196,20 @@ def main():
         B.nanospec_vocab_init(st.h, d_ctx, coff, d_T0, toff, stream)
         for s_ in range(Wm):
             step(s_, s_, stream)
+    if args.only_union:
+        # counter runs: only the two head kernels of the batch-union head appear in the trace besides the set-up
+        su = B.State(V, d, Bn, seqs["window"], seqs["topk_cap"], M, k)
+        B.nanospec_union_enable(su.h, args.only_union, 0)
+        B.nanospec_vocab_init(su.h, d_ctx, coff, d_T0, toff, stream)
+        B.nanospec_union_build(su.h, stream)
+        for i in range(Wm + K):
+            B.nanospec_union_head(su.h, Wd[i % R], Hd[i % NH], M, logits, stream)
+        torch.cuda.synchronize()
+        sid, spos, rest, share, scap = su.read_union()
+        print(json.dumps({"only_union": True, "min_share": share, "launches": Wm + K, "shared_rows": len(sid),
+                          "pairs_shared": int((spos >= 0).sum()), "pairs_rest": int(sum(len(r[0]) for r in rest))}))
+        su.close()
+        return
     ms, ms_all = timed(step, Wm, K, reset=reset_main)
     n_active = [len(a) for a in st.read_active()]
     n_sum = int(np.sum(n_active))
@@ -203,8 +221,14 @@ def main():
     head = lambda i, r, cs: B.nanospec_sparse_head(st.h, Wd[r % R], Hd[r % NH], M, logits, cs)
     head_us = timed(head, 0, NL)[0] * 1e3 / NL
     alg_bytes = n_sum * d * 2                                  # gathered weight bytes per launch
+    # Several sequences hold many of the same rows; those are served by the caches, so the gathered bytes can exceed
+    # what HBM delivers.  The roofline of a batch is quoted on the distinct rows (what must come from HBM at least
+    # once per launch); the gathered rate is reported beside it.
+    distinct_rows = int(len(np.unique(np.concatenate(st.read_active())))) if Bn > 1 else n_sum
+    roof_bytes = distinct_rows * d * 2
     log("head alone timed")
-    achieved = alg_bytes / (head_us * 1e-6) / 1e9
+    achieved = roof_bytes / (head_us * 1e-6) / 1e9
+    gathered = alg_bytes / (head_us * 1e-6) / 1e9
 
     def train(fn, n=200, reset=None):
         """median us per call of a back-to-back train of n calls"""
@@ -343,6 +367,35 @@ def main():
         for q in pst:
             q.close()
 
+    # Several sequences: the batch-union head (ids held by at least min_share sequences are fetched once and meet all
+    # hidden rows, the others stay per sequence) against the per-sequence head, on the state the context leaves;
+    # same cold rotation and timing.  build = the two list kernels, which need no hidden states.
+    union_variant = None
+    if Bn > 1 and not args.no_union:
+        sweep = {}
+        best = None
+        for share in [int(x) for x in args.union_shares.split(",") if 0 < int(x) <= Bn]:
+            su = B.State(V, d, Bn, seqs["window"], seqs["topk_cap"], M, k)
+            B.nanospec_union_enable(su.h, share, 0)
+            B.nanospec_vocab_init(su.h, d_ctx, coff, d_T0, toff, stream)
+            B.nanospec_union_build(su.h, stream)
+            sid, spos, rest, _, _ = su.read_union()
+            uh = train(lambda i, r, cs: B.nanospec_union_head(su.h, Wd[r % R], Hd[r % NH], M, logits, cs), 2 * ROT)
+            ub = train(lambda i, r, cs: B.nanospec_union_build(su.h, cs), 64)
+            sweep[str(share)] = {"shared_rows": len(sid), "pairs_shared": int((spos >= 0).sum()),
+                                 "pairs_per_sequence": int(sum(len(r[0]) for r in rest)), "head_us": round(uh, 2), "build_us": round(ub, 2)}
+            if best is None or uh < best[1]:
+                best = (share, uh, ub)
+            su.close()
+        s0 = B.State(V, d, Bn, seqs["window"], seqs["topk_cap"], M, k)
+        B.nanospec_vocab_init(s0.h, d_ctx, coff, d_T0, toff, stream)
+        base_us = train(lambda i, r, cs: B.nanospec_sparse_head(s0.h, Wd[r % R], Hd[r % NH], M, logits, cs), 2 * ROT)
+        s0.close()
+        union_variant = {"per_sequence_head_us": round(base_us, 2), "by_min_share": sweep, "best_min_share": best[0],
+                         "best_head_us": round(best[1], 2), "best_head_plus_build_us": round(best[1] + best[2], 2),
+                         "speedup_head": round(base_us / best[1], 3), "speedup_head_plus_build": round(base_us / (best[1] + best[2]), 3)}
+        log("batch-union head timed")
+
     log("ceilings and packed-buffer variant timed")
     # the one-off stream initialisation (S(0) = context, T = T0; clear + apply kernels), on a scratch state
     st_i = B.State(V, d, Bn, seqs["window"], seqs["topk_cap"], M, k)
@@ -440,19 +493,22 @@ def main():
                                f"window={seqs['window']} |T|={len(seqs['T0'][0])} accept={cfg['acc']}",
                    "replicas_of_W": R, "weights": "cold (rotated)" if R > 1 else "warm",
                    "launch": "hip graph replay" if use_graph else "eager"},
-        "gathered_GBps": round(achieved, 1),
+        "gathered_GBps": round(gathered, 1),
         "roofline": {"bound": "hbm", "kernel": "nanospec_sparse_head", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": float(args.traffic) if args.traffic else (
                          round(PMC_TRAFFIC_PER_ROW[pmc_key] * n_sum) if pmc_key in PMC_TRAFFIC_PER_ROW else None),
                      "traffic_source": "quoted, not measured by this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
                                        "command summarised under profiles/, scaled per active row",
-                     "bytes_per_launch": alg_bytes, "us_per_launch": round(head_us, 3)},
+                     "bytes_per_launch": roof_bytes, "us_per_launch": round(head_us, 3),
+                     "bytes_note": None if Bn == 1 else f"distinct rows of the batch ({distinct_rows} of {n_sum} gathered): rows that "
+                                                         "several sequences hold come from HBM once and from the caches afterwards"},
         "ceilings": ceilings, "cold_check": cold_check,
         "kernels_us": {"vocab_update": round(upd_us, 2), "sparse_head": round(head_us, 2), "topk_remap": round(topk_us, 2)},
         "vocab_init_us": round(init_us, 2),
         "closed_loop": closed,
         "packed_buffer_variant": packed_variant,
+        "batch_union_head": union_variant,
         "vocabulary_policies": policy_compare,
         "dense": dense,
         "cpu_baseline": cpu,

@@ -222,8 +222,11 @@ NANOSPEC_API nanospec_status nanospec_packed_view(const nanospec_state* st, cons
  *                           vocabulary call and before nanospec_union_head; it needs no hidden states, so it may run
  *                           beside the draft backbone.  Asynchronous.  Errors: EINVAL (not enabled), EHIP.
  *   nanospec_union_head   : d_logits fp32 [batch][M][capacity] as nanospec_sparse_head (entries j >= n_b
- *                           unspecified), from d_W_bf16 [V][d] and d_H_bf16 [batch][M][d].  Asynchronous.
- *                           Errors: EINVAL, ECAPACITY (M > m_cap).
+ *                           unspecified), from d_W_bf16 [V][d] and d_H_bf16 [batch][M][d].  The shared-row product
+ *                           runs on a stream the state owns (default priority), forked from `hip_stream` and joined
+ *                           back into it by events before the call returns its work to `hip_stream`; a graph
+ *                           capture of `hip_stream` records both branches.  Two calls on one state must not
+ *                           overlap.  Asynchronous.  Errors: EINVAL, ECAPACITY (M > m_cap), EHIP.
  *   nanospec_union_view   : borrowed device views for inspection: shared ids [shared_cap] and their number
  *                           (first entry of d_shared_n), shared_pos [batch][shared_cap] (column or -1), rest ids
  *                           and columns [batch][capacity], rest_n [batch]; any pointer may be NULL. */

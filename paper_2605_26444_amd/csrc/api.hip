@@ -186,7 +186,13 @@ nanospec_status nanospec_create(nanospec_state** out, int32_t V, int32_t d, int3
 nanospec_status nanospec_destroy(nanospec_state* st) {
   if (!st) return NANOSPEC_EINVAL;
   if (st->pk_base) (void)hipFree(st->pk_base);
-  if (st->un_base) (void)hipFree(st->un_base);
+  if (st->un_base) {
+    (void)hipStreamSynchronize(st->un_side);
+    (void)hipEventDestroy(st->un_fork);
+    (void)hipEventDestroy(st->un_join);
+    (void)hipStreamDestroy(st->un_side);
+    (void)hipFree(st->un_base);
+  }
   hipError_t e1 = hipFree(st->base);
   hipError_t e2 = hipHostFree(st->h_err_pinned);
   delete st;
@@ -293,7 +299,22 @@ nanospec_status nanospec_union_enable(nanospec_state* st, int32_t min_share, int
   u.rest_pos = reinterpret_cast<int32_t*>(take(B * cap * 4));
   u.rest_n = reinterpret_cast<int32_t*>(take(B * 4));
   st->un_base = base;
-  if (p - base > bytes || launch_union_reset(st, nullptr) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+  bool ok = p - base <= bytes && hipStreamCreateWithFlags(&st->un_side, hipStreamNonBlocking) == hipSuccess;
+  if (ok) {
+    ok = hipEventCreateWithFlags(&st->un_fork, hipEventDisableTiming) == hipSuccess;
+    if (ok) {
+      ok = hipEventCreateWithFlags(&st->un_join, hipEventDisableTiming) == hipSuccess;
+      if (!ok) (void)hipEventDestroy(st->un_fork);
+    }
+    if (!ok) (void)hipStreamDestroy(st->un_side);
+  }
+  if (ok && (launch_union_reset(st, nullptr) != hipSuccess || hipDeviceSynchronize() != hipSuccess)) {
+    (void)hipEventDestroy(st->un_fork);
+    (void)hipEventDestroy(st->un_join);
+    (void)hipStreamDestroy(st->un_side);
+    ok = false;
+  }
+  if (!ok) {
     (void)hipGetLastError();
     (void)hipFree(base);
     st->un_base = nullptr;
@@ -314,14 +335,20 @@ nanospec_status nanospec_union_head(nanospec_state* st, const void* d_W_bf16, co
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const UnionPtrs& u = st->un;
   const int32_t cap = st->vp.cap;
+  // The two products are independent and write disjoint columns.  The shared one is few workgroups that each walk
+  // all of K (latency-bound), the per-sequence one many short workgroups (throughput-bound): the first runs on the
+  // state's side stream (default priority), forked from and joined back into the caller's stream by events, so a
+  // graph capture of the caller's stream records both branches.
+  if (hipEventRecord(st->un_fork, s) != hipSuccess || hipStreamWaitEvent(st->un_side, st->un_fork, 0) != hipSuccess) return NANOSPEC_EHIP;
   // shared rows: fetched once, multiplied with every sequence's hidden rows, scattered to each sequence's columns
   hipError_t e = launch_head_shared(d_W_bf16, d_H_bf16, u.shared_ids, u.shared_n, u.shared_cap, st->V, st->batch * M, M, st->d, cap,
-                                    d_logits, u.shared_pos, u.shared_cap, s);
+                                    d_logits, u.shared_pos, u.shared_cap, st->un_side);
+  if (hipEventRecord(st->un_join, st->un_side) != hipSuccess) return NANOSPEC_EHIP;   // joined even after a failed launch
   // the rest per sequence, exactly as nanospec_sparse_head but on the shorter lists
-  if (e == hipSuccess)
-    e = launch_head(d_W_bf16, d_H_bf16, u.rest_ids, u.rest_n, 0, cap, st->V, st->batch, M, st->d, cap, cap, d_logits, st->partial,
-                    st->partial_bytes, u.rest_pos, s);
-  return e == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;
+  hipError_t e2 = launch_head(d_W_bf16, d_H_bf16, u.rest_ids, u.rest_n, 0, cap, st->V, st->batch, M, st->d, cap, cap, d_logits,
+                              st->partial, st->partial_bytes, u.rest_pos, s);
+  if (hipStreamWaitEvent(s, st->un_join, 0) != hipSuccess) return NANOSPEC_EHIP;
+  return e == hipSuccess && e2 == hipSuccess ? NANOSPEC_OK : NANOSPEC_EHIP;
 }
 
 nanospec_status nanospec_union_view(const nanospec_state* st, const int32_t** d_shared_ids, const int32_t** d_shared_n,

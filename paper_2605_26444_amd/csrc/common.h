@@ -75,6 +75,8 @@ struct nanospec_state {
   nanospec::UnionPtrs un;        // batch-union head; un_base == nullptr until nanospec_union_enable
   char* un_base;
   int32_t un_groups;             // groups of 64 hidden rows at M = m_cap
+  hipStream_t un_side;           // the shared-row product runs here, beside the per-sequence product
+  hipEvent_t un_fork, un_join;
 };
 
 namespace nanospec {

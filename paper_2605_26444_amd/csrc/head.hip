@@ -310,6 +310,15 @@ __global__ __launch_bounds__(256 * NRG) void head_quad_kernel(const uint16_t* __
   int vzero = 0;
   if (UNCOND) asm volatile("" : "+v"(vzero));             // a zero the compiler cannot see through: keeps the load below on the vector path
   const int n = n_dev ? n_dev[b + vzero] : n_fixed;
+  // Many sequences (row groups of 8): the launch is sized by the capacity, typically twice the live row count, and
+  // the work is throughput-bound -- a workgroup whose rows all lie past the end leaves before it pulls its 64 KB of
+  // hidden rows (measured on 64 sequences of 2.3k rows in lists of capacity 5120: a workgroup without rows cost
+  // 0.65 of one with rows; 178 -> 130 us).  Measured on top of this and not kept: a workgroup walking 2-8
+  // consecutive tiles with the hidden-row operands resident in LDS (125 us at 2 tiles, slower beyond; with the next
+  // tile's weight loads issued before the epilogue 136 us), and handing each of the chip's eight dies one eighth of
+  // every sequence's list so that the sequences' copies of a row meet in one L2 (more fabric traffic, not less:
+  // every die then needs all sequences' hidden rows in its L2).
+  if (!UNCOND && tile * (NRG * RPG) >= n) return;
   // where the logit this thread will store goes (see head_quad_private_kernel); asked for now, used at the end
   static_assert(NOUT <= 256, "one output per thread");
   int jout = -1;

@@ -75,6 +75,7 @@ hipError_t ensure_device_configured() {
   if (e == hipSuccess) e = vocab_configure_device();
   if (e == hipSuccess) e = calib_configure_device();
   if (e == hipSuccess) e = union_configure_device();
+  if (e == hipSuccess) e = wide_configure_device();
   if (e == hipSuccess) g_cfg_done[dev] = true;
   return e;
 }

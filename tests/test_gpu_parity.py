@@ -542,6 +542,8 @@ def test_step_recorded_in_hip_graph_replays_correctly():
     # last tile and with hidden rows that do not; the last sequence's hidden rows end the H buffer
     (8192, 32, 70, 2), (1024, 17, 1000, 1), (2048, 48, 300, 2), (1024, 64, 2000, 1), (512, 64, 17000, 1), (512, 40, 17000, 1),
     (8192, 12, 1300, 1), (8192, 10, 500, 2), (6144, 16, 9000, 1), (4096, 3, 100, 1),
+    # the register-blocked product on a gathered list (at least 16384 rows of capacity, d a multiple of 128): both block shapes
+    (512, 70, 17000, 1), (1024, 130, 16500, 1), (128, 17, 19999, 1), (384, 64, 16400, 1),
 ])
 def test_head_shapes_against_oracle(d, M, n_ctx, batch):
     """every head kernel and its ragged tails: row counts that are not multiples of the tile, hidden sizes that

@@ -162,6 +162,63 @@ def check_shared(rows_total, seq_rows, d, cap_rows, opos_stride, nseq=None):
                         need(q * opos_stride + j + 3 < nseq * opos_stride, "column table", q, j)
 
 
+def check_wide(M, d, V, n, cap_rows, ld, ids_len=None):
+    """head_wide_kernel (csrc/wide.hip): BM x BN blocks of logits, K in steps of BK, both operand blocks through LDS."""
+    need(M > 16 and d % 128 == 0, "launcher's condition")
+    WR, WH, FR, FH, BK = (4, 1, 2, 4, 64) if M <= 64 else (4, 2, 4, 4, 64)
+    NT = 64 * WR * WH
+    BM, BN = WR * FR * 16, WH * FH * 16
+    CPR = BK // 8
+    RPP = NT // CPR
+    NA, NB = BM // RPP, BN // RPP
+    STR = BK * 2 + 32
+    STAGE = (BM + BN) * STR
+    lds = 2 * STAGE
+    need(lds <= 160 * 1024 and BM % RPP == 0 and BN % RPP == 0 and d % (2 * BK) == 0, "tile shape, an even number of steps")
+    row_blocks, hid_blocks = ceil_div(cap_rows, BM), ceil_div(M, BN)
+    grid = ceil_div(row_blocks, 8) * hid_blocks * 8
+    seen = set()
+    tid = np.arange(NT)
+    pc, pr = tid % CPR, tid // CPR
+    lane, w = tid & 63, tid >> 6
+    wr, wh = w // WH, w % WH
+    for blk in range(grid):
+        xq, xr = blk & 7, blk >> 3
+        hb, rb = xr % hid_blocks, (xr // hid_blocks) * 8 + xq
+        if rb >= row_blocks:
+            continue
+        seen.add((rb, hb))
+        if rb not in (0, row_blocks - 1, (n - 1) // BM if n else 0) or hb not in (0, hid_blocks - 1):
+            continue
+        j0, m0 = rb * BM, hb * BN
+        if j0 >= n:
+            continue
+        for i in range(NA):
+            j = j0 + pr + i * RPP
+            if ids_len is not None:
+                need(np.all(j[j < n] < ids_len), "ids", j.max(), ids_len)
+            # rows are clamped into [0, V) or replaced by row 0; the column bytes:
+            need(np.all(pc * 16 + (d // BK - 1) * BK * 2 + 16 <= d * 2), "W column")
+            need(np.all((pr + i * RPP) * STR + pc * 16 + 16 <= BM * STR), "LDS park A")
+        for i in range(NB):
+            m = np.minimum(m0 + pr + i * RPP, M - 1)
+            need(np.all((m >= 0) & (m < M)), "H row")
+            need(np.all((pr + i * RPP) * STR + pc * 16 + 16 <= BN * STR), "LDS park B")
+        frag = (lane & 15) * STR + (lane >> 4) * 16
+        for kk in range(BK // 32):
+            need(np.all((wr * FR * 16 + (FR - 1) * 16) * STR + frag + kk * 64 + 16 <= BM * STR), "LDS read A")
+            need(np.all(BM * STR + (wh * FH * 16 + (FH - 1) * 16) * STR + frag + kk * 64 + 16 <= STAGE), "LDS read B")
+        for a in range(FR):
+            j = j0 + (wr * FR + a) * 16 + 4 * (lane >> 4)
+            for b_ in range(FH):
+                m = m0 + (wh * FH + b_) * 16 + (lane & 15)
+                ok = (m < M) & (j < n)
+                vec = ok & (ld % 4 == 0) & (j + 3 < n)
+                need(np.all((m * ld + j + 3)[vec] < M * ld), "vector store")
+                need(np.all((j + 3)[vec] < ld), "row end")
+    need(seen == {(r, h) for r in range(row_blocks) for h in range(hid_blocks)}, "every block is visited once", len(seen))
+
+
 def check(M, d, batch, cap, V, n, dense):
     for variant, prm in plan(M, d, batch, cap, dense):
         if variant == "quad":
@@ -198,6 +255,18 @@ def test_shared_list_launches_stay_inside_their_buffers():
         check_shared(160, 8, 4096, 64, 64, nseq=19)
     with pytest.raises(OutOfBounds):
         check_shared(160, 8, 4096, 96, 96)
+
+
+@pytest.mark.parametrize("V", [16384, 50001, 128256, 152064])
+def test_register_blocked_product_stays_inside_its_buffers(V):
+    for M, d in itertools.product((17, 32, 64, 65, 70, 128, 130, 512), (128, 3584, 4096, 8192)):
+        check_wide(M, d, V, V, V, V)                                   # the dense head
+        for n in (1, 127, 128, 129, 16384, V - 1):                     # a long id list of capacity V
+            check_wide(M, d, V, n, V, V, ids_len=V)
+    with pytest.raises(OutOfBounds):
+        check_wide(64, 3592, 152064, 152064, 152064, 152064)           # d not a whole number of steps
+    with pytest.raises(OutOfBounds):
+        check_wide(64, 4096, 20000, 20000, 20000, 19996)               # logits rows shorter than the row count
 
 
 def test_the_selection_that_once_faulted_is_rejected():

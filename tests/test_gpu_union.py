@@ -172,3 +172,70 @@ def test_union_c4_shape():
     st = _run(cfg["V"], cfg["d"], cfg["M"], cfg["k"], seqs["window"], seqs["ctx"], seqs["T0"], steps, W, 9990, min_share=0,
               sample_seqs=(0, 31, 63))
     assert min(st["shared"]) > 1000
+
+
+def test_union_step_recorded_in_hip_graph_replays_correctly():
+    """update + list build + union head (whose shared-row product forks onto the state's side stream and joins back) +
+    selection captured in one HIP graph: every replay, with eager work and synchronisations in between, gives the
+    oracle's vocabulary, the eager union head's bits and the oracle's logits."""
+    rng = np.random.default_rng(26)
+    V, d, M, k, window, nb = 8000, 512, 8, 6, 128, 12
+    W = synth.normal_bf16(9991, 0, (V, d), 0.02)
+    ctx, T0, _ = _random_case(rng, V, nb, 400, 50, 250, 0)
+    dW = dev_bf16(W)
+    H = synth.normal_bf16(9992, 0, (nb, M, d), 1.0, threads=1)
+    dH = dev_bf16(H)
+    st = B.State(V, d, nb, window, 64, M, k)
+    B.nanospec_union_enable(st.h, 3, 0)
+    orc = [oracle.Vocab(V, window) for _ in range(nb)]
+    flat, off = csr(ctx)
+    tflat, toff = csr(T0)
+    B.nanospec_vocab_init(st.h, dev_ids(flat), off, dev_ids(tflat), toff)
+    for b in range(nb):
+        orc[b].init(ctx[b], T0[b])
+    new = [rng.integers(0, 250, 3).astype(np.int32) for _ in range(nb)]
+    nflat, noff = csr(new)
+    d_new = dev_ids(nflat)
+    cap = st.capacity
+    lg_g = torch.empty((nb, M, cap), dtype=torch.float32, device="cuda")
+    lg_e = torch.empty_like(lg_g)
+    oi_g = torch.empty((nb, M, k), dtype=torch.int32, device="cuda")
+    ov_g = torch.empty((nb, M, k), dtype=torch.float32, device="cuda")
+    oi_e, ov_e = torch.empty_like(oi_g), torch.empty_like(ov_g)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        cs = torch.cuda.current_stream().cuda_stream
+        B.nanospec_vocab_update(st.h, d_new, noff, None, None, cs)
+        B.nanospec_union_build(st.h, cs)
+        B.nanospec_union_head(st.h, dW, dH, M, lg_g, cs)
+        B.nanospec_topk_remap(st.h, lg_g, M, k, oi_g, ov_g, cs)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        lg_g.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        for b in range(nb):
+            orc[b].update(new[b])
+        act = st.read_active()
+        for b in range(nb):
+            assert np.array_equal(act[b], orc[b].active()), (rep, b)
+        lg_e.fill_(float("nan"))
+        B.nanospec_union_head(st.h, dW, dH, M, lg_e)                   # eager work between replays
+        B.nanospec_topk_remap(st.h, lg_e, M, k, oi_e, ov_e)
+        torch.cuda.synchronize()
+        gg, ge = lg_g.cpu().numpy(), lg_e.cpu().numpy()
+        for b in range(nb):
+            n = len(act[b])
+            assert not np.isnan(gg[b, :, :n]).any(), (rep, b)
+            assert np.array_equal(gg[b, :, :n], ge[b, :, :n]), (rep, b)
+            o32, o64 = oracle.head(W, H[b], ids=act[b], omp=True)
+            assert_logits_close(gg[b, :, :n], o64, o32, f"replay {rep} seq {b}")
+        assert np.array_equal(oi_g.cpu().numpy(), oi_e.cpu().numpy()) and np.array_equal(ov_g.cpu().numpy(), ov_e.cpu().numpy())
+        extra = [np.array([rep, 7000 + rep], np.int32) for _ in range(nb)]   # eager update between replays
+        ef, eo = csr(extra)
+        B.nanospec_vocab_update(st.h, dev_ids(ef), eo)
+        for b in range(nb):
+            orc[b].update(extra[b])
+    assert B.nanospec_last_device_error(st.h) == 0
+    st.close()

@@ -16,7 +16,7 @@ from harness import assert_logits_close, check_topk, csr, dev_bf16, dev_ids, hos
 pytestmark = pytest.mark.gpu
 
 
-def _run(V, d, M, k, window, ctx, T0, steps, W, seed, min_share, shared_cap=0, m_cap=None, sample_seqs=None):
+def _run(V, d, M, k, window, ctx, T0, steps, W, seed, min_share, shared_cap=0, m_cap=None, sample_seqs=None, fifo=False):
     """ctx, T0: per-sequence lists; steps: list of (per-sequence appended ids, per-sequence new T or None)."""
     nb = len(ctx)
     dW = dev_bf16(W)
@@ -24,11 +24,13 @@ def _run(V, d, M, k, window, ctx, T0, steps, W, seed, min_share, shared_cap=0, m
     st = B.State(V, d, nb, window, topk_cap, m_cap or M, k)
     assert B.nanospec_union_bytes(st.h, shared_cap) > 0
     B.nanospec_union_enable(st.h, min_share, shared_cap)
+    if fifo:
+        B.nanospec_set_stream_policy(st.h, B.POLICY_FIFO)
     cap = st.capacity
     logits = torch.empty((nb, M, cap), dtype=torch.float32, device="cuda")
     oi = torch.empty((nb, M, k), dtype=torch.int32, device="cuda")
     ov = torch.empty((nb, M, k), dtype=torch.float32, device="cuda")
-    orc = [oracle.Vocab(V, window) for _ in range(nb)]
+    orc = [(oracle.FifoVocab if fifo else oracle.Vocab)(V, window) for _ in range(nb)]
     flat, off = csr(ctx)
     tflat, toff = csr(T0)
     B.nanospec_vocab_init(st.h, dev_ids(flat), off, dev_ids(tflat), toff)
@@ -108,6 +110,16 @@ def test_union_small_tail_group_only():
     ctx, T0, steps = _random_case(rng, V, 6, 300, 40, 150, 6)
     st = _run(V, d, M, k, window, ctx, T0, steps, W, 9200, min_share=3)
     assert min(st["shared"]) > 0 and 0 < st["pairs_shared"] < st["pairs"]
+
+
+def test_union_under_the_queue_reading_of_the_vocabulary():
+    """the lists are built from the membership bitmaps, which both readings of the vocabulary maintain"""
+    rng = np.random.default_rng(27)
+    V, d, M, k, window = 6000, 512, 4, 6, 80
+    W = synth.normal_bf16(9150, 0, (V, d), 0.02)
+    ctx, T0, steps = _random_case(rng, V, 9, 300, 40, 150, 5)
+    st = _run(V, d, M, k, window, ctx, T0, steps, W, 9250, min_share=3, fifo=True)
+    assert min(st["shared"]) > 0
 
 
 def test_union_groups_and_tail_hidden_size_not_a_whole_slice():

@@ -149,8 +149,8 @@ __global__ __launch_bounds__(64 * WR * WH) void head_wide_kernel(const uint16_t*
     }
     // The order above is the order wanted; left alone, the scheduler puts every fragment read right in front of its
     // first use.  Groups: the LDS reads of the next fragment(s), then FH matrix instructions.  Only for the
-    // compute-bound shape (eight wavefronts): 644 -> 614 us at 512 hidden rows; the memory-bound four-wavefront
-    // shape loses with it (205 -> 218 us at 64 hidden rows).
+    // compute-bound shapes (eight wavefronts): 644 -> 614 us at 512 hidden rows on 256 x 128 logits; the memory-bound
+    // four-wavefront shape loses with it (205 -> 218 us at 64 hidden rows).
     if constexpr (WR * WH == 8) {
       __builtin_amdgcn_sched_group_barrier(0x100, FH + 1, 0);
 #pragma unroll
@@ -222,7 +222,8 @@ static hipError_t run_wide(const uint16_t* W, const uint16_t* H, const int32_t* 
 }
 
 hipError_t wide_configure_device() {
-  const void* fns[] = {reinterpret_cast<const void*>(head_wide_kernel<4, 2, 4, 4, 64>), reinterpret_cast<const void*>(head_wide_kernel<4, 1, 2, 4, 64>)};
+  const void* fns[] = {reinterpret_cast<const void*>(head_wide_kernel<4, 1, 2, 4, 64>), reinterpret_cast<const void*>(head_wide_kernel<4, 2, 4, 4, 64>),
+                       reinterpret_cast<const void*>(head_wide_kernel<2, 4, 8, 4, 64>)};
   for (const void* f : fns) {
     hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
@@ -234,16 +235,21 @@ bool wide_supported(int32_t M, int32_t d, int32_t batch) { return batch == 1 && 
 
 // One sequence (or the dense head), more than 16 hidden rows, d a multiple of 128.
 //   up to 64 hidden rows: memory-bound.  128 x 64 logits per workgroup of four wavefronts, 60 KB of LDS, two workgroups
-//     per compute unit (dense 152k x 3584 head at 64 hidden rows: 205 us, the vendor GEMM 206, 5.3 TB/s; 256-byte
+//     per compute unit (dense 152k x 3584 head at 64 hidden rows: 205-219 us, the vendor GEMM 205-208, 5.2 TB/s; 256-byte
 //     steps with one workgroup per compute unit: 209 us).
-//   more: compute-bound.  256 x 128 logits per workgroup of eight wavefronts, 64 x 64 per wavefront (four wavefronts
-//     of 128 x 64 with one wavefront per SIMD: 844 us at 512 hidden rows against 614).
+//   up to 128: 256 x 128 logits, eight wavefronts of 64 x 64.
+//   more: compute-bound.  256 x 256 logits per workgroup, eight wavefronts of 128 x 64 (one fragment read feeds four or
+//     eight matrix instructions), all 160 KB of LDS for the two stages.  512 hidden rows on the 128k x 4096 matrix:
+//     516 us = 1.04 PFLOP/s, the vendor GEMM 510.  On the way there: four wavefronts of 128 x 64 on 256 x 128 logits
+//     844 us (one wavefront per SIMD: nothing overlaps an LDS round trip), eight of 64 x 64 644 us, with the
+//     scheduling groups 614 us, 256 x 256 logits in 32-column steps 553 us.
 hipError_t launch_head_wide(const void* W, const void* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed, int32_t cap_rows,
                             int32_t V, int32_t M, int32_t d, int64_t ld, float* logits, hipStream_t s) {
   const uint16_t* Wp = static_cast<const uint16_t*>(W);
   const uint16_t* Hp = static_cast<const uint16_t*>(H);
   if (M <= 64) return run_wide<4, 1, 2, 4, 64>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, M, d, ld, logits, s);
-  return run_wide<4, 2, 4, 4, 64>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, M, d, ld, logits, s);
+  if (M <= 128) return run_wide<4, 2, 4, 4, 64>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, M, d, ld, logits, s);
+  return run_wide<2, 4, 8, 4, 64>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, M, d, ld, logits, s);
 }
 
 }  // namespace nanospec

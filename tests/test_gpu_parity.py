@@ -149,7 +149,8 @@ def test_dense_entries_c4_comparator_many_hidden_rows(M_total):
     _dense_entries_against_oracle(host_W(cfg), cfg["V"], cfg["d"], M_total, cfg["k"], 4100 + M_total, n_sample=600)
 
 
-@pytest.mark.parametrize("d,M_total", [(512, 5), (512, 16), (1024, 40), (520, 40), (512, 70), (1032, 130), (8192, 16), (4096, 12)])
+@pytest.mark.parametrize("d,M_total", [(512, 5), (512, 16), (1024, 40), (520, 40), (512, 70), (1032, 130), (8192, 16), (4096, 12),
+                                        (1024, 130), (512, 300), (128, 257)])   # the register-blocked kernel's three block shapes, scalar stores
 def test_dense_entries_row_stride_not_a_multiple_of_four(d, M_total):
     """V = 50001: logit rows start at odd addresses (the per-element store branch of the head kernels, the scalar
     load branch of the selection) and the last row tile is ragged."""

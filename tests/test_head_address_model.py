@@ -165,7 +165,7 @@ def check_shared(rows_total, seq_rows, d, cap_rows, opos_stride, nseq=None):
 def check_wide(M, d, V, n, cap_rows, ld, ids_len=None):
     """head_wide_kernel (csrc/wide.hip): BM x BN blocks of logits, K in steps of BK, both operand blocks through LDS."""
     need(M > 16 and d % 128 == 0, "launcher's condition")
-    WR, WH, FR, FH, BK = (4, 1, 2, 4, 64) if M <= 64 else (4, 2, 4, 4, 64)
+    WR, WH, FR, FH, BK = (4, 1, 2, 4, 64) if M <= 64 else ((4, 2, 4, 4, 64) if M <= 128 else (2, 4, 8, 4, 64))
     NT = 64 * WR * WH
     BM, BN = WR * FR * 16, WH * FH * 16
     CPR = BK // 8
@@ -259,7 +259,7 @@ def test_shared_list_launches_stay_inside_their_buffers():
 
 @pytest.mark.parametrize("V", [16384, 50001, 128256, 152064])
 def test_register_blocked_product_stays_inside_its_buffers(V):
-    for M, d in itertools.product((17, 32, 64, 65, 70, 128, 130, 512), (128, 3584, 4096, 8192)):
+    for M, d in itertools.product((17, 32, 64, 65, 70, 128, 129, 130, 256, 257, 512), (128, 3584, 4096, 8192)):
         check_wide(M, d, V, V, V, V)                                   # the dense head
         for n in (1, 127, 128, 129, 16384, V - 1):                     # a long id list of capacity V
             check_wide(M, d, V, n, V, V, ids_len=V)

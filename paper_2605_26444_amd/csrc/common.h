@@ -104,11 +104,11 @@ hipError_t launch_head_shared(const void* W, const void* H, const int32_t* ids, 
                               int32_t rows_total, int32_t seq_rows, int32_t d, int64_t ld_logits, float* logits, const int32_t* opos,
                               int64_t opos_stride, hipStream_t s);
 
-// wide.hip: register-blocked product for many hidden rows of one sequence / the dense head (d % 128 == 0, M > 16)
-bool wide_supported(int32_t M, int32_t d, int32_t batch);
+// wide.hip: register-blocked product for more than 16 hidden rows of one sequence / the dense head
+bool wide_supported(int32_t M, int32_t d, int32_t batch, int32_t cap_rows);
 hipError_t wide_configure_device();
 hipError_t launch_head_wide(const void* W, const void* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed, int32_t cap_rows,
-                            int32_t V, int32_t M, int32_t d, int64_t ld, float* logits, hipStream_t s);
+                            int32_t V, int32_t M, int32_t d, int64_t ld, float* logits, const int32_t* opos, hipStream_t s);
 
 // union.hip
 hipError_t union_configure_device();

@@ -757,7 +757,6 @@ hipError_t launch_head_shared(const void* W, const void* H, const int32_t* ids, 
 // first stateless call on the device, never in a launch path -- so that no later call can lower it under a live
 // state and no asynchronous call makes a runtime call that is not a launch.
 constexpr int kLdsLimit = 160 * 1024;
-constexpr int kWideRowsMin = 16384;   // below this the row blocks of the register-blocked product cannot fill the chip
 
 template <int MT, int KS>
 static hipError_t configure_quad() {
@@ -801,10 +800,10 @@ hipError_t launch_head(const void* W, const void* H, const int32_t* ids, const i
                        float* logits, float* partial, int64_t partial_bytes, const int32_t* opos, hipStream_t s) {
   const uint16_t* Wp = static_cast<const uint16_t*>(W);
   const uint16_t* Hp = static_cast<const uint16_t*>(H);
-  // many rows and more than 16 hidden rows (the dense comparison point of wide trees and batches): the
-  // register-blocked product, which reads W_head once per 64 / 128 hidden rows
-  if (opos == nullptr && cap_rows >= kWideRowsMin && wide_supported(M, d, batch))
-    return launch_head_wide(W, H, ids, n_dev, n_fixed, cap_rows, V, M, d, ld_logits, logits, s);
+  // more than 16 hidden rows of one sequence: the register-blocked product wherever it is the faster one (many rows: the
+  // dense comparison point of wide trees and batches; a few thousand rows: wide trees, instead of split-K + reduce)
+  if (wide_supported(M, d, batch, cap_rows))
+    return launch_head_wide(W, H, ids, n_dev, n_fixed, cap_rows, V, M, d, ld_logits, logits, opos, s);
   if (M <= 64)
     return launch_head_64(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld_logits, ids_stride, logits, partial,
                           partial_bytes, opos, s);

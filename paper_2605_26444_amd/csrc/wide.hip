@@ -20,15 +20,16 @@ constexpr int kWidePad = 32;     // bytes between LDS rows: rows r and r+4 share
 
 // WR x WH wavefronts (4 or 8); a wavefront owns FR x FH fragments of 16 x 16 logits.
 //   logits[m][j] for hidden row m < M and list row j < n, row stride ld.  ids == nullptr: rows 0..n-1.
+//   opos != nullptr ([opos_len], a multiple of 4 entries): row j's logits go to column opos[j] instead, nowhere if negative.
 // d % BK == 0 (checked by the launcher).  Rows past n read row 0, hidden rows past M read row M-1; neither is stored.
 // Workgroup order: the chip hands consecutive workgroups to its eight dies in turn and each die has its own L2, so
 // the hidden-row blocks of one row block run back to back on one die (blockIdx -> (row block, hidden block) below)
 // and find the row block's weights in that L2.
-template <int WR, int WH, int FR, int FH, int BK>
+template <int WR, int WH, int FR, int FH, int BK, int D>
 __global__ __launch_bounds__(64 * WR * WH) void head_wide_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
                                                         const int32_t* __restrict__ ids, const int32_t* __restrict__ n_dev, int n_fixed,
                                                         int V, int M, int d, int64_t ld, float* __restrict__ logits, int row_blocks,
-                                                        int hid_blocks) {
+                                                        int hid_blocks, const int32_t* __restrict__ opos, int opos_len) {
   constexpr int NT = 64 * WR * WH;
   constexpr int BM = WR * FR * 16, BN = WH * FH * 16;
   constexpr int CPR = BK / 8;                      // 16-byte pieces per row and step
@@ -78,9 +79,10 @@ __global__ __launch_bounds__(64 * WR * WH) void head_wide_kernel(const uint16_t*
   const char* Wb = reinterpret_cast<const char*>(W);
   const char* Hbase = reinterpret_cast<const char*>(H);
 
-  // two register sets: the loads of step ks+2 are issued before the matrix work of step ks starts, so a load has
-  // two steps' time to arrive (one step of matrix work is shorter than an HBM round trip)
-  u32x4 ga[2][NA], gb[2][NB];
+  // D register sets: the loads of step s+D are issued before the matrix work of step s starts, so a load has D
+  // steps' time to arrive (one step of matrix work is shorter than an HBM round trip) and D-1 sets -- (D-1) x (BM+BN)
+  // x BK x 2 bytes -- are in flight per workgroup all the time
+  u32x4 ga[D][NA], gb[D][NB];
   auto fetch = [&](int ks, int set) {
     const uint32_t off = (uint32_t)ks * BK * 2;
 #pragma unroll
@@ -165,28 +167,27 @@ __global__ __launch_bounds__(64 * WR * WH) void head_wide_kernel(const uint16_t*
     }
   };
 
-  // nk is even and at least 2 (the launcher checks d % (2 * BK) == 0).  Every fetch is unconditional -- past the end
-  // the last step is fetched again and never used -- because a load under a branch makes the number of loads in
-  // flight unknowable at compile time, and every wait for one register set then becomes a wait for both.
+  // Every fetch is unconditional -- past the end the last step is fetched again and never used -- because a load
+  // under a branch makes the number of loads in flight unknowable at compile time, and every wait for one register
+  // set then becomes a wait for all of them.  Set s % D receives step s + D right after it was parked for step s.
+  // D == 2: nk is even (the launcher checks d % (2 * BK) == 0) and the loop body has no branch at all; D > 2: any nk,
+  // the steps past the end skip their matrix work (a uniform branch around LDS reads and matrix instructions only).
   const int nk = d / BK;
-  fetch(0, 0);
-  fetch(1, 1);
+#pragma unroll
+  for (int j = 0; j < D; ++j) fetch(j < nk ? j : nk - 1, j);
   __builtin_amdgcn_sched_barrier(0);
   park(0, 0);
   __syncthreads();
-  for (int ks = 0; ks < nk; ks += 2) {
-    // step ks: LDS stage 0 holds it, set 1 holds (or awaits) step ks+1
-    fetch(ks + 2 < nk ? ks + 2 : nk - 1, 0);
-    __builtin_amdgcn_sched_barrier(0);              // the loads go out before the matrix work, not after it
-    multiply(0);
-    park(1, 1);                                     // stage 1's last readers passed the previous barrier
-    __syncthreads();
-    // step ks+1
-    fetch(ks + 3 < nk ? ks + 3 : nk - 1, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    multiply(1);
-    park(0, 0);
-    __syncthreads();
+  for (int ks = 0; ks < nk; ks += D) {
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+      const int st = ks + j;                        // LDS stage j & 1 holds this step, set (j + 1) % D holds (or awaits) the next
+      fetch(st + D < nk ? st + D : nk - 1, j);
+      __builtin_amdgcn_sched_barrier(0);            // the loads go out before the matrix work, not after it
+      if (D == 2 || st < nk) multiply(j & 1);
+      park((j + 1) & 1, (j + 1) % D);               // that stage's last readers passed the previous barrier
+      __syncthreads();
+    }
   }
 
   // result lane l holds list rows j + v (v = 0..3), j = 4 * (l / 16), of hidden row l % 16 of the fragment
@@ -198,7 +199,14 @@ __global__ __launch_bounds__(64 * WR * WH) void head_wide_kernel(const uint16_t*
       const int m = m0 + (wh * FH + b) * 16 + (lane & 15);
       if (m >= M || j >= n) continue;
       float* dst = logits + (int64_t)m * ld + j;
-      if ((ld & 3) == 0 && j + 3 < n) {
+      if (opos) {                                       // rows kept in an order of their own: list row j's logits go to column opos[j]
+        const int4 jo4 = j + 3 < opos_len ? *reinterpret_cast<const int4*>(opos + j) : make_int4(-1, -1, -1, -1);
+        const int jo[4] = {jo4.x, jo4.y, jo4.z, jo4.w};
+        float* rowp = logits + (int64_t)m * ld;
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          if (j + v < n && jo[v] >= 0) rowp[jo[v]] = acc[a][b][v];
+      } else if ((ld & 3) == 0 && j + 3 < n) {
         *reinterpret_cast<f32x4*>(dst) = acc[a][b];
       } else {
 #pragma unroll
@@ -209,21 +217,21 @@ __global__ __launch_bounds__(64 * WR * WH) void head_wide_kernel(const uint16_t*
   }
 }
 
-template <int WR, int WH, int FR, int FH, int BK>
+template <int WR, int WH, int FR, int FH, int BK, int D>
 static hipError_t run_wide(const uint16_t* W, const uint16_t* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed, int32_t cap_rows,
-                           int32_t V, int32_t M, int32_t d, int64_t ld, float* logits, hipStream_t s) {
+                           int32_t V, int32_t M, int32_t d, int64_t ld, float* logits, const int32_t* opos, hipStream_t s) {
   constexpr int BM = WR * FR * 16, BN = WH * FH * 16;
   constexpr int LDS = 2 * (BM + BN) * (BK * 2 + kWidePad);
   const int row_blocks = (cap_rows + BM - 1) / BM, hid_blocks = (M + BN - 1) / BN;
   const int64_t grid = (int64_t)((row_blocks + 7) / 8) * hid_blocks * 8;
   if (grid > 0x7fffffff || (int64_t)V * d * 2 > 0xffffffffll || (int64_t)M * d * 2 > 0xffffffffll) return hipErrorInvalidValue;
-  head_wide_kernel<WR, WH, FR, FH, BK><<<dim3((unsigned)grid), 64 * WR * WH, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, logits, row_blocks, hid_blocks);
+  head_wide_kernel<WR, WH, FR, FH, BK, D><<<dim3((unsigned)grid), 64 * WR * WH, LDS, s>>>(W, H, ids, n_dev, n_fixed, V, M, d, ld, logits, row_blocks, hid_blocks, opos, cap_rows / 4 * 4);
   return hipGetLastError();
 }
 
 hipError_t wide_configure_device() {
-  const void* fns[] = {reinterpret_cast<const void*>(head_wide_kernel<4, 1, 2, 4, 64>), reinterpret_cast<const void*>(head_wide_kernel<4, 2, 4, 4, 64>),
-                       reinterpret_cast<const void*>(head_wide_kernel<2, 4, 8, 4, 64>)};
+  const void* fns[] = {reinterpret_cast<const void*>(head_wide_kernel<4, 1, 2, 4, 64, 2>), reinterpret_cast<const void*>(head_wide_kernel<4, 2, 4, 4, 64, 2>),
+                       reinterpret_cast<const void*>(head_wide_kernel<2, 4, 8, 4, 64, 2>), reinterpret_cast<const void*>(head_wide_kernel<2, 2, 1, 1, 256, 2>)};
   for (const void* f : fns) {
     hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
@@ -231,25 +239,42 @@ hipError_t wide_configure_device() {
   return hipSuccess;
 }
 
-bool wide_supported(int32_t M, int32_t d, int32_t batch) { return batch == 1 && M > 16 && d % 128 == 0; }   // an even number of 64-column steps
+// Which row capacities the register-blocked product takes (one sequence or the dense head, 16 < M, no column map):
+//   at least 16384 rows and d % 128 == 0: the three block shapes of launch_head_wide below;
+//   a few thousand rows, M <= 64 and d % 512 == 0: the 32 x 32 shape (no split of K, one launch) from the capacity on
+//   at which it beats split-K + reduce (measured at d = 3584, M = 64 / 32, live rows = capacity: 8.9 against 10.7 us
+//   at 1000 rows, 11.6 / 11.7 at 2000, 14.9 / 12.3 at 3000, 25.4 / 21.2 at 8000; M = 32: 12.7 / 12.4 at 3000, 17.6 / 13.3
+//   at 5000).
+bool wide_supported(int32_t M, int32_t d, int32_t batch, int32_t cap_rows) {
+  if (batch != 1 || M <= 16) return false;
+  if (cap_rows >= 16384) return d % 128 == 0;                    // an even number of 64-column steps
+  return M <= 64 && d % 512 == 0 && cap_rows >= (M <= 32 ? 4096 : 2560);
+}
 
-// One sequence (or the dense head), more than 16 hidden rows, d a multiple of 128.
-//   up to 64 hidden rows: memory-bound.  128 x 64 logits per workgroup of four wavefronts, 60 KB of LDS, two workgroups
-//     per compute unit (dense 152k x 3584 head at 64 hidden rows: 205-219 us, the vendor GEMM 205-208, 5.2 TB/s; 256-byte
-//     steps with one workgroup per compute unit: 209 us).
+// One sequence (or the dense head), more than 16 hidden rows.
+//   a few thousand rows (wide draft trees): latency-bound.  32 x 32 logits per workgroup of four wavefronts, 256-column
+//     steps (512 bytes of a row per load pass, 64 KB in flight per workgroup) -- the rows alone cannot fill the chip,
+//     so the hidden rows are split in two as well.  3000 rows x 64 hidden rows, d = 3584: 12.2 us in one launch against
+//     10 + 4 us for split-K and its reduce.  The time is the 458 KB every workgroup pulls through its compute unit's
+//     L1 (11.7 us without any matrix work); three or four register sets in flight instead of two: 13.6 / 14.1 us;
+//     128-column steps 13.6; 64 x 16 logits 14.9.
+//   many rows, up to 64 hidden rows: memory-bound.  128 x 64 logits per workgroup of four wavefronts, 60 KB of LDS, two
+//     workgroups per compute unit (dense 152k x 3584 head at 64 hidden rows: 205-219 us, the vendor GEMM 205-208,
+//     5.2 TB/s; 256-byte steps with one workgroup per compute unit: 209 us).
 //   up to 128: 256 x 128 logits, eight wavefronts of 64 x 64.
 //   more: compute-bound.  256 x 256 logits per workgroup, eight wavefronts of 128 x 64 (one fragment read feeds four or
 //     eight matrix instructions), all 160 KB of LDS for the two stages.  512 hidden rows on the 128k x 4096 matrix:
-//     516 us = 1.04 PFLOP/s, the vendor GEMM 510.  On the way there: four wavefronts of 128 x 64 on 256 x 128 logits
-//     844 us (one wavefront per SIMD: nothing overlaps an LDS round trip), eight of 64 x 64 644 us, with the
+//     516-539 us = 1.0 PFLOP/s, the vendor GEMM 510-513.  On the way there: four wavefronts of 128 x 64 on 256 x 128
+//     logits 844 us (one wavefront per SIMD: nothing overlaps an LDS round trip), eight of 64 x 64 644 us, with the
 //     scheduling groups 614 us, 256 x 256 logits in 32-column steps 553 us.
 hipError_t launch_head_wide(const void* W, const void* H, const int32_t* ids, const int32_t* n_dev, int32_t n_fixed, int32_t cap_rows,
-                            int32_t V, int32_t M, int32_t d, int64_t ld, float* logits, hipStream_t s) {
+                            int32_t V, int32_t M, int32_t d, int64_t ld, float* logits, const int32_t* opos, hipStream_t s) {
   const uint16_t* Wp = static_cast<const uint16_t*>(W);
   const uint16_t* Hp = static_cast<const uint16_t*>(H);
-  if (M <= 64) return run_wide<4, 1, 2, 4, 64>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, M, d, ld, logits, s);
-  if (M <= 128) return run_wide<4, 2, 4, 4, 64>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, M, d, ld, logits, s);
-  return run_wide<2, 4, 8, 4, 64>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, M, d, ld, logits, s);
+  if (cap_rows < 16384) return run_wide<2, 2, 1, 1, 256, 2>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, M, d, ld, logits, opos, s);
+  if (M <= 64) return run_wide<4, 1, 2, 4, 64, 2>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, M, d, ld, logits, opos, s);
+  if (M <= 128) return run_wide<4, 2, 4, 4, 64, 2>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, M, d, ld, logits, opos, s);
+  return run_wide<2, 4, 8, 4, 64, 2>(Wp, Hp, ids, n_dev, n_fixed, cap_rows, V, M, d, ld, logits, opos, s);
 }
 
 }  // namespace nanospec

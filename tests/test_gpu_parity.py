@@ -545,6 +545,8 @@ def test_step_recorded_in_hip_graph_replays_correctly():
     (8192, 12, 1300, 1), (8192, 10, 500, 2), (6144, 16, 9000, 1), (4096, 3, 100, 1),
     # the register-blocked product on a gathered list (at least 16384 rows of capacity, d a multiple of 128): both block shapes
     (512, 70, 17000, 1), (1024, 130, 16500, 1), (128, 17, 19999, 1), (384, 64, 16400, 1),
+    # ... and its 32 x 32 shape on a few thousand rows (d a multiple of 512; from 2560 rows of capacity, 4096 up to 32 hidden rows)
+    (512, 64, 3000, 1), (1024, 40, 4000, 1), (512, 24, 5000, 1), (3584, 64, 2600, 1), (1024, 33, 2561, 1), (512, 17, 9000, 1),
 ])
 def test_head_shapes_against_oracle(d, M, n_ctx, batch):
     """every head kernel and its ragged tails: row counts that are not multiples of the tile, hidden sizes that

@@ -162,10 +162,22 @@ def check_shared(rows_total, seq_rows, d, cap_rows, opos_stride, nseq=None):
                         need(q * opos_stride + j + 3 < nseq * opos_stride, "column table", q, j)
 
 
+def wide_supported(M, d, batch, cap_rows):
+    """mirror of the launcher's choice of the register-blocked product (csrc/wide.hip)"""
+    if batch != 1 or M <= 16:
+        return False
+    if cap_rows >= 16384:
+        return d % 128 == 0
+    return M <= 64 and d % 512 == 0 and cap_rows >= (4096 if M <= 32 else 2560)
+
+
 def check_wide(M, d, V, n, cap_rows, ld, ids_len=None):
     """head_wide_kernel (csrc/wide.hip): BM x BN blocks of logits, K in steps of BK, both operand blocks through LDS."""
-    need(M > 16 and d % 128 == 0, "launcher's condition")
-    WR, WH, FR, FH, BK = (4, 1, 2, 4, 64) if M <= 64 else ((4, 2, 4, 4, 64) if M <= 128 else (2, 4, 8, 4, 64))
+    need(wide_supported(M, d, 1, cap_rows), "launcher's condition")
+    if cap_rows < 16384:
+        WR, WH, FR, FH, BK = 2, 2, 1, 1, 256
+    else:
+        WR, WH, FR, FH, BK = (4, 1, 2, 4, 64) if M <= 64 else ((4, 2, 4, 4, 64) if M <= 128 else (2, 4, 8, 4, 64))
     NT = 64 * WR * WH
     BM, BN = WR * FR * 16, WH * FH * 16
     CPR = BK // 8
@@ -220,6 +232,9 @@ def check_wide(M, d, V, n, cap_rows, ld, ids_len=None):
 
 
 def check(M, d, batch, cap, V, n, dense):
+    if wide_supported(M, d, batch, cap):
+        check_wide(M, d, V, n, cap, V if dense else cap, ids_len=None if dense else cap)
+        return
     for variant, prm in plan(M, d, batch, cap, dense):
         if variant == "quad":
             check_quad(M, d, batch, cap, V, n, dense, **prm)
@@ -263,6 +278,12 @@ def test_register_blocked_product_stays_inside_its_buffers(V):
         check_wide(M, d, V, V, V, V)                                   # the dense head
         for n in (1, 127, 128, 129, 16384, V - 1):                     # a long id list of capacity V
             check_wide(M, d, V, n, V, V, ids_len=V)
+    for M, d, cap in itertools.product((17, 32, 33, 48, 64), (512, 3584, 4096, 8192), (2560, 4096, 4352, 16320)):
+        if wide_supported(M, d, 1, cap):
+            for n in (0, 1, 31, 32, 33, cap // 2 + 1, cap):            # the 32 x 32 shape on a few thousand gathered rows
+                check_wide(M, d, 152064, n, cap, cap, ids_len=cap)
+    assert wide_supported(64, 3584, 1, 4352) and not wide_supported(64, 3584, 1, 2048) and not wide_supported(32, 3584, 1, 2560)
+    assert not wide_supported(64, 3592, 1, 4352) and not wide_supported(64, 3584, 2, 4352) and not wide_supported(16, 4096, 1, 152064)
     with pytest.raises(OutOfBounds):
         check_wide(64, 3592, 152064, 152064, 152064, 152064)           # d not a whole number of steps
     with pytest.raises(OutOfBounds):

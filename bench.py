@@ -39,7 +39,7 @@ HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
 # profiles/ (FETCH_SIZE x 2.0 +
 # WRITE_SIZE x 1.0, factors from copy / stream kernels of known size), as bytes per active row so that it
 # follows the realised |active|.  c3: the split-K kernel without its reduce kernel; c5: measured at 32k rows.
-PMC_TRAFFIC_PER_ROW = {"c2": 25313690 / 3004, "c3": 30672896 / 2998, "c4": 767895347 / 144911,
+PMC_TRAFFIC_PER_ROW = {"c2": 25313690 / 3004, "c3": 25943859 / 2998, "c4": 767895347 / 144911,
                        "c5@32000": 533476454 / 32007}
 
 

@@ -152,6 +152,11 @@ __global__ __launch_bounds__(64 * NW) void head_quad_private_kernel(const uint16
   static_assert(RT * MT * 16 <= 64 * NW, "one output per thread");
   int jout = j0 + (threadIdx.x / (MT * 16)) * 4 + (threadIdx.x % 16) / 4;
   if (opos) jout = threadIdx.x < RT * MT * 16 && jout < (int)ids_stride ? opos[b * ids_stride + jout] : -1;
+  // A tile past the end leaves before it pulls any hidden rows: the launch is sized by the capacity, and with long
+  // rows (this kernel's case) a tile's share of the hidden rows is as many bytes as its weights.  (Measured on the
+  // sparsity sweep at d = 8192, capacities 2.6 to 7.4 times the live rows: 10.2 -> 9.7, 16.4 -> 15.7, 31.1 -> 29.2,
+  // 109.5 -> 99.5 us; with live rows = capacity nothing changes: 7.02 / 10.7 / 16.9 / 26.2 us at 1000 - 6000 rows.)
+  if (j0 >= n) return;
   // hidden rows of the first K-iteration depend on the arguments only: they stream in from L2
   // while the ids are still on their way
   u32x4 hv[MT][KS];
@@ -164,7 +169,6 @@ __global__ __launch_bounds__(64 * NW) void head_quad_private_kernel(const uint16
     row = row < 0 ? 0 : (row >= V ? V - 1 : row);
     wrow[rt] = W + row * d;
   }
-  if (j0 >= n) return;
 
   f32x4 acc[RT][MT];
 #pragma unroll

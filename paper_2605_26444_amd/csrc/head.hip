@@ -453,13 +453,21 @@ static hipError_t run_quad_auto(const uint16_t* W, const uint16_t* H, const int3
                                 int64_t ids_stride, float* logits, const int32_t* opos, hipStream_t s) {
   const int64_t rows = (int64_t)cap_rows * batch;
   if (d > 512 * KS) {
-    if (rows < 8 * 180) return run_quad_private<1, MT, KS, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
+    // (tiles past the end leave at once in this kernel, so what counts is the live rows: 4 rows per workgroup while they
+    // fit 256 workgroups -- about 0.8 of the capacity in the workloads here; 7.0 us at 1000 live rows, 10.1 us at 1091)
+    if (rows <= 5 * 256) return run_quad_private<1, MT, KS, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
     if (MT <= 2 || rows < 8192) return run_quad_private<2, MT, KS, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
     return run_quad_private<4, MT, KS, 4>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
   }
   if (batch > 1 && rows >= 8192) return run_quad<2, 2, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
-  if (rows >= 16 * 180) return run_quad<4, 1, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
-  if (rows >= 8 * 180) return run_quad<2, 1, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
+  // 16 / 8 / 4 rows per workgroup: the coarsest shape that still gives every workgroup of the launch (sized by the
+  // capacity) a compute unit of its own.  A workgroup without rows costs as much as one with rows here (its loads
+  // are unconditional), so one workgroup more than the chip has compute units puts two on one unit and the launch
+  // waits for that unit: measured at d = 4096, M = 8, live rows = 0.8 capacity, 8 rows per workgroup: 4.85 us at
+  // capacity 2048 (256 workgroups), 6.30 us at 2304 (288); with the earlier thresholds (1440 / 2880 rows) capacity
+  // 1280 took 4.88 us (now 4.00) and 2752 took 7.50 us (now 6.52).
+  if (rows > 8 * 256) return run_quad<4, 1, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
+  if (rows > 4 * 256) return run_quad<2, 1, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
   return run_quad<1, 1, MT, KS>(W, H, ids, n_dev, n_fixed, cap_rows, V, batch, M, d, ld, ids_stride, logits, opos, s);
 }
 

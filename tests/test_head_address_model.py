@@ -42,13 +42,13 @@ def plan(M, d, batch, cap, dense, partial_bytes=1 << 62):
         else:
             MT, KS = (4, 8) if 2048 < d <= 4096 else (4, 4)
         if d > 512 * KS:
-            RT = 1 if rows < 8 * 180 else (2 if (MT <= 2 or rows < 8192) else 4)
+            RT = 1 if rows <= 5 * 256 else (2 if (MT <= 2 or rows < 8192) else 4)
             return [("private", dict(RT=RT, MT=MT, KS=KS, NW=4, fast=d % (4 * 128 * KS) == 0))]
         if batch > 1 and rows >= 8192:
             NRG, RT = 2, 2
-        elif rows >= 16 * 180:
+        elif rows > 8 * 256:
             NRG, RT = 4, 1
-        elif rows >= 8 * 180:
+        elif rows > 4 * 256:
             NRG, RT = 2, 1
         else:
             NRG, RT = 1, 1

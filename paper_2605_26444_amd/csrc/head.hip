@@ -319,7 +319,8 @@ __global__ __launch_bounds__(256 * NRG) void head_quad_kernel(const uint16_t* __
   // hidden rows (measured on 64 sequences of 2.3k rows in lists of capacity 5120: a workgroup without rows cost
   // 0.65 of one with rows; 178 -> 130 us).  Measured on top of this and not kept: a workgroup walking 2-8
   // consecutive tiles with the hidden-row operands resident in LDS (125 us at 2 tiles, slower beyond; with the next
-  // tile's weight loads issued before the epilogue 136 us), and handing each of the chip's eight dies one eighth of
+  // tile's weight loads issued before the epilogue 136 us; as a kernel of its own with two register sets of weights,
+  // every load unconditional and the tile loop fully unrolled, one workgroup per compute unit: 135 us), and handing each of the chip's eight dies one eighth of
   // every sequence's list so that the sequences' copies of a row meet in one L2 (more fabric traffic, not less:
   // every die then needs all sequences' hidden rows in its L2).
   if (!UNCOND && tile * (NRG * RPG) >= n) return;

@@ -1002,3 +1002,28 @@ def test_randomised_head_shapes():
                 assert np.array_equal(gli[b, m], ei), (case, b, m)
                 assert np.all(np.abs(glv[b, m][fin].astype(np.float64) - elp[fin]) <= 1e-4), (case, b, m)
         st.close()
+
+
+@pytest.mark.parametrize("cap,M,d", [(3000, 64, 512), (5000, 24, 1024), (17000, 64, 256), (17000, 130, 128)])
+def test_wide_tree_head_on_nearly_empty_lists(cap, M, d):
+    """the register-blocked shapes are chosen by the capacity; the list may hold no row, one row, or one row more than a block"""
+    V = 20000
+    W = synth.normal_bf16(7700 + d, 0, (V, d), 0.02)
+    H = synth.normal_bf16(7701 + d, M, (1, M, d), 1.0, threads=1)
+    dW, dH = dev_bf16(W), dev_bf16(H)
+    for n in (0, 1, 33, 257):
+        st = B.State(V, d, 1, cap, 0, M, 4)
+        ids = np.sort(np.random.default_rng(n + d).choice(V, size=n, replace=False)).astype(np.int32)
+        ctx = np.concatenate([ids, ids[:1].repeat(7)]) if n else ids
+        B.nanospec_vocab_init(st.h, dev_ids(ctx), [0, len(ctx)], None, [0, 0])
+        logits = torch.full((1, M, st.capacity), float("nan"), dtype=torch.float32, device="cuda")
+        B.nanospec_sparse_head(st.h, dW, dH, M, logits)
+        torch.cuda.synchronize()
+        assert np.array_equal(st.read_active()[0], ids)
+        g = logits.cpu().numpy()[0]
+        assert np.isnan(g[:, n:]).all(), "a column past the row count was written"
+        if n:
+            o32, o64 = oracle.head(W, H[0], ids=ids, omp=True)
+            assert_logits_close(g[:, :n], o64, o32, f"cap={cap} M={M} d={d} n={n}")
+        assert B.nanospec_last_device_error(st.h) == 0
+        st.close()

@@ -122,6 +122,16 @@ def test_union_under_the_queue_reading_of_the_vocabulary():
     assert min(st["shared"]) > 0
 
 
+def test_union_more_sequences_than_a_wavefront_has_lanes():
+    """130 sequences: the per-id count walks the batch in chunks of 64 lanes; 130 x 2 hidden rows = 4 groups and a tail of 4"""
+    rng = np.random.default_rng(28)
+    V, d, M, k, window = 2000, 256, 2, 3, 48
+    W = synth.normal_bf16(9160, 0, (V, d), 0.02)
+    ctx, T0, steps = _random_case(rng, V, 130, 120, 10, 60, 2)
+    st = _run(V, d, M, k, window, ctx, T0, steps, W, 9260, min_share=70)
+    assert min(st["shared"]) > 0 and st["pairs_shared"] < st["pairs"]
+
+
 def test_union_groups_and_tail_hidden_size_not_a_whole_slice():
     """20 sequences x 8 hidden rows = two groups of 64 and a tail of 32; d = 1032 takes the bounds-tested loads"""
     rng = np.random.default_rng(22)

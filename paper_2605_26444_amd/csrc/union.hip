@@ -100,7 +100,7 @@ __global__ __launch_bounds__(kListThreads) void union_lists_kernel(VocabPtrs p, 
         bits &= bits - 1u;
       }
     }
-    if (tid < groups) u.shared_n[tid] = ns;
+    for (int g = tid; g < groups; g += kListThreads) u.shared_n[g] = ns;
   }
   int32_t* mypos = u.shared_pos + (size_t)b * u.shared_cap;
   for (int r = tid; r < u.shared_cap; r += kListThreads) mypos[r] = -1;

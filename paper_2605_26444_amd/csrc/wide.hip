@@ -38,6 +38,7 @@ __global__ __launch_bounds__(64 * WR * WH) void head_wide_kernel(const uint16_t*
   constexpr int STR = BK * 2 + kWidePad;           // LDS row stride in bytes
   constexpr int STAGE = (BM + BN) * STR;
   static_assert(BM % RPP == 0 && BN % RPP == 0, "whole passes");
+  static_assert(D >= 2 && D % 2 == 0, "step s reads LDS stage s & 1: the unrolled group of D steps must keep that parity");
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
   // blockIdx -> die x = blockIdx % 8, slot r = blockIdx / 8; hidden block = r % hid_blocks, row block = (r / hid_blocks) * 8 + x
@@ -170,7 +171,7 @@ __global__ __launch_bounds__(64 * WR * WH) void head_wide_kernel(const uint16_t*
   // Every fetch is unconditional -- past the end the last step is fetched again and never used -- because a load
   // under a branch makes the number of loads in flight unknowable at compile time, and every wait for one register
   // set then becomes a wait for all of them.  Set s % D receives step s + D right after it was parked for step s.
-  // D == 2: nk is even (the launcher checks d % (2 * BK) == 0) and the loop body has no branch at all; D > 2: any nk,
+  // D == 2: nk is even (the launcher checks d % (2 * BK) == 0) and the loop body has no branch at all; D = 4, 6, ..: any nk,
   // the steps past the end skip their matrix work (a uniform branch around LDS reads and matrix instructions only).
   const int nk = d / BK;
 #pragma unroll
